@@ -1,0 +1,197 @@
+"""Pins for the oracle's attention values, log-sum-exp and decode (CPU only).
+
+The oracle is checked against: a pure-Python triple loop of Equation 1 on tiny
+inputs, a library routine (torch's scaled_dot_product_attention in float64) in
+the special case where the pattern degenerates to full causal attention, closed
+forms (zero keys, constant values, the first row) and invariances.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import powattn_oracle as orc
+from oracle.powattn_oracle import Pattern
+from paper_2503_03588_amd import synth
+from test_oracle_pattern import brute_pair
+
+
+def _rand(shape, seed):
+    return np.random.default_rng(seed).standard_normal(shape)
+
+
+def loop_attention(q, k, v, B, W, S, power, scale):
+    """Equation 1 with explicit Python loops and math.exp."""
+    batch, hq, n, d = q.shape
+    g = hq // k.shape[1]
+    o = np.zeros((batch, hq, n, d))
+    lse = np.zeros((batch, hq, n))
+    for b in range(batch):
+        for h in range(hq):
+            for i in range(n):
+                js = [j for j in range(n) if brute_pair(i, j, B, W, S, power)]
+                logits = [scale * sum(q[b, h, i, c] * k[b, h // g, j, c] for c in range(d)) for j in js]
+                z = sum(math.exp(x) for x in logits)
+                for x, j in zip(logits, js):
+                    w = math.exp(x) / z
+                    for c in range(d):
+                        o[b, h, i, c] += w * v[b, h // g, j, c]
+                lse[b, h, i] = math.log(z)
+    return o, lse
+
+
+@pytest.mark.parametrize("B,W,S,power", [(4, 2, 1, True), (3, 1, 0, True), (4, 3, 1, False), (5, 2, 2, True)])
+def test_against_python_loops(B, W, S, power):
+    batch, hq, hkv, n, d = 2, 4, 2, 37, 5
+    q, k, v = _rand((batch, hq, n, d), 1), _rand((batch, hkv, n, d), 2), _rand((batch, hkv, n, d), 3)
+    pat = Pattern(block=B, window=W, sink=S, power=power)
+    o, lse = orc.attention(q, k, v, pat)
+    o2, lse2 = loop_attention(q, k, v, B, W, S, power, 1.0 / math.sqrt(d))
+    assert np.abs(o - o2).max() < 1e-12
+    assert np.abs(lse - lse2).max() < 1e-12
+    # an explicit scale is honoured
+    o3, lse3 = orc.attention(q, k, v, pat, scale=0.3)
+    o4, lse4 = loop_attention(q, k, v, B, W, S, power, 0.3)
+    assert np.abs(o3 - o4).max() < 1e-12 and np.abs(lse3 - lse4).max() < 1e-12
+
+
+@pytest.mark.parametrize("hq,hkv", [(4, 4), (8, 2), (6, 1)])
+def test_window_covering_sequence_equals_library_causal_attention(hq, hkv):
+    batch, n, d = 2, 96, 16
+    q, k, v = _rand((batch, hq, n, d), 4), _rand((batch, hkv, n, d), 5), _rand((batch, hkv, n, d), 6)
+    pat = Pattern(block=8, window=12, sink=1)       # W*B = N: every causal pair is in the window
+    o, lse = orc.attention(q, k, v, pat)
+    tq, tk, tv = (torch.from_numpy(x) for x in (q, k, v))
+    g = hq // hkv
+    tk, tv = tk.repeat_interleave(g, dim=1), tv.repeat_interleave(g, dim=1)
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True)
+    assert np.abs(o - ref.numpy()).max() < 1e-12
+    s = (tq @ tk.transpose(-1, -2)) / math.sqrt(d)
+    s = s.masked_fill(~torch.tril(torch.ones(n, n, dtype=torch.bool)), float("-inf"))
+    assert np.abs(lse - torch.logsumexp(s, dim=-1).numpy()).max() < 1e-12
+    # the dense flag gives the same thing with any window
+    o2, lse2 = orc.attention(q, k, v, Pattern(block=8, window=1, sink=0, dense=True))
+    assert np.abs(o - o2).max() < 1e-13 and np.abs(lse - lse2).max() < 1e-13
+
+
+def test_zero_keys_give_mean_of_attended_values_and_log_count():
+    batch, hq, hkv, n, d, B, W, S = 1, 2, 1, 80, 4, 8, 2, 1
+    q = _rand((batch, hq, n, d), 7)
+    k = np.zeros((batch, hkv, n, d))
+    v = _rand((batch, hkv, n, d), 8)
+    o, lse = orc.attention(q, k, v, Pattern(block=B, window=W, sink=S))
+    for i in range(n):
+        js = [j for j in range(n) if brute_pair(i, j, B, W, S)]
+        assert np.abs(o[0, :, i] - v[0, 0, js].mean(axis=0)).max() < 1e-13
+        assert np.abs(lse[0, :, i] - math.log(len(js))).max() < 1e-13
+
+
+def test_constant_values_and_first_row():
+    batch, hq, hkv, n, d = 1, 2, 2, 64, 8
+    q, k = _rand((batch, hq, n, d), 9), _rand((batch, hkv, n, d), 10)
+    v = np.broadcast_to(_rand((1, hkv, 1, d), 11), (batch, hkv, n, d)).copy()
+    pat = Pattern(block=4, window=2, sink=1)
+    o, lse = orc.attention(q, k, v, pat)
+    assert np.abs(o - v[:, :, :1]).max() < 1e-13
+    v2 = _rand((batch, hkv, n, d), 12)
+    o2, lse2 = orc.attention(q, k, v2, pat)
+    assert np.abs(o2[:, :, 0] - v2[:, :, 0]).max() < 1e-15                  # row 0 sees only itself
+    want = (q[:, :, 0] * k[:, :, 0]).sum(-1) / math.sqrt(d)
+    assert np.abs(lse2[:, :, 0] - want).max() < 1e-13
+
+
+def test_rows_subset_equals_full():
+    batch, hq, hkv, n, d = 1, 4, 2, 100, 8
+    q, k, v = _rand((batch, hq, n, d), 13), _rand((batch, hkv, n, d), 14), _rand((batch, hkv, n, d), 15)
+    pat = Pattern(block=8, window=2, sink=1)
+    o, lse = orc.attention(q, k, v, pat)
+    rows = [0, 7, 8, 55, 99]
+    o2, lse2 = orc.attention_rows(q, k, v, rows, pat)
+    assert np.array_equal(o[:, :, rows], o2) and np.array_equal(lse[:, :, rows], lse2)
+
+
+def test_decode_equals_prefill_row():
+    batch, hq, hkv, cap, d = 3, 4, 2, 120, 8
+    k, v = _rand((batch, hkv, cap, d), 16), _rand((batch, hkv, cap, d), 17)
+    qfull = _rand((batch, hq, cap, d), 18)
+    pat = Pattern(block=8, window=2, sink=1)
+    kv_len = np.array([120, 57, 1])
+    qd = np.stack([qfull[b, :, kv_len[b] - 1] for b in range(batch)])
+    o, lse = orc.decode(qd, k, v, kv_len, pat)
+    for b in range(batch):
+        L = kv_len[b]
+        of, lf = orc.attention(qfull[b:b + 1, :, :L], k[b:b + 1, :, :L], v[b:b + 1, :, :L], pat)
+        assert np.abs(o[b] - of[0, :, L - 1]).max() < 1e-13
+        assert np.abs(lse[b] - lf[0, :, L - 1]).max() < 1e-13
+
+
+def test_permuting_keys_inside_a_fully_visible_block_changes_nothing():
+    batch, hq, hkv, n, d, B = 1, 2, 1, 64, 8, 8
+    q, k, v = _rand((batch, hq, n, d), 19), _rand((batch, hkv, n, d), 20), _rand((batch, hkv, n, d), 21)
+    pat = Pattern(block=B, window=2, sink=1)
+    o, lse = orc.attention(q, k, v, pat)
+    perm = np.arange(n)
+    perm[0:B] = perm[0:B][::-1]             # shuffle the sink block's tokens
+    o2, lse2 = orc.attention(q, k[:, :, perm], v[:, :, perm], pat)
+    rows = np.arange(B, n)                   # rows for which block 0 is not the diagonal block
+    assert np.abs(o[:, :, rows] - o2[:, :, rows]).max() < 1e-13
+    assert np.abs(lse[:, :, rows] - lse2[:, :, rows]).max() < 1e-13
+
+
+def test_unattended_keys_have_no_influence():
+    batch, hq, hkv, n, d, B = 1, 1, 1, 128, 4, 8
+    q, k, v = _rand((batch, hq, n, d), 22), _rand((batch, hkv, n, d), 23), _rand((batch, hkv, n, d), 24)
+    pat = Pattern(block=B, window=2, sink=1)
+    o, _ = orc.attention_rows(q, k, v, [127], pat)
+    k2, v2 = k.copy(), v.copy()
+    blk = 5                                   # distance 10 from block 15: not window, not power, not sink
+    k2[:, :, blk * B:(blk + 1) * B] += 100.0
+    v2[:, :, blk * B:(blk + 1) * B] -= 50.0
+    o2, _ = orc.attention_rows(q, k2, v2, [127], pat)
+    assert np.array_equal(o, o2)
+    blk = 7                                   # distance 8: attended
+    k2, v2 = k.copy(), v.copy()
+    v2[:, :, blk * B:(blk + 1) * B] -= 50.0
+    o3, _ = orc.attention_rows(q, k, v2, [127], pat)
+    assert np.abs(o - o3).max() > 1e-3
+
+
+def test_bf16_bits_are_widened_exactly():
+    t = synth.gaussian((3, 5, 7), "bf16", seed=5)
+    bits = synth.to_numpy_storage(t)
+    assert bits.dtype == np.uint16
+    assert np.array_equal(orc.widen(bits), t.double().numpy())
+    f = synth.gaussian((4, 4), "f32", seed=6)
+    assert np.array_equal(orc.widen(synth.to_numpy_storage(f)), f.double().numpy())
+
+
+def test_synth_is_deterministic_and_seeded():
+    a = synth.gaussian((8, 8), "f32", seed=0)
+    b = synth.gaussian((8, 8), "f32", seed=0)
+    c = synth.gaussian((8, 8), "f32", seed=1)
+    assert torch.equal(a, b) and not torch.equal(a, c)
+    q, k, v = synth.qkv(1, 4, 2, 16, 8, "bf16", seed=3)
+    assert q.shape == (1, 4, 16, 8) and k.shape == (1, 2, 16, 8) and v.dtype == torch.bfloat16
+    assert not torch.equal(k, v)
+
+
+def test_planted_mistakes_in_softmax_are_caught(monkeypatch):
+    good = orc._softmax_rows
+
+    def no_max_in_lse(s, allowed, v):          # lse without adding the row maximum back
+        o, lse = good(s, allowed, v)
+        return o, lse - np.where(allowed, s, -np.inf).max(axis=1)
+
+    def unnormalised(s, allowed, v):           # forgets the division by l
+        o, lse = good(s, allowed, v)
+        return o * np.exp(lse)[:, None], lse
+
+    def mask_after_exp(s, allowed, v):         # masks with 0 logits instead of -inf
+        return good(np.where(allowed, s, 0.0), np.ones_like(allowed), v)
+
+    for bad in (no_max_in_lse, unnormalised, mask_after_exp):
+        monkeypatch.setattr(orc, "_softmax_rows", bad)
+        with pytest.raises(AssertionError):
+            test_against_python_loops(4, 2, 1, True)
+        monkeypatch.setattr(orc, "_softmax_rows", good)
