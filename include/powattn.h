@@ -1,0 +1,169 @@
+/*
+ * powattn.h -- C ABI of the MI355X (gfx950) PowerAttention forward library.
+ *
+ * The library computes causal block-sparse attention under the static pattern
+ * of the PowerAttention paper (arXiv 2503.03588): every query block attends a
+ * local window of key blocks, the key blocks at power-of-two block distances,
+ * and the first ("sink") blocks of the sequence.
+ *
+ * Conventions for every entry point
+ *   - "device" pointers are HIP device memory of the current device; "host"
+ *     pointers are ordinary process memory.  The library never allocates,
+ *     frees or keeps any pointer; the caller owns every buffer.
+ *   - Device work is enqueued on `hip_stream` (a hipStream_t passed as void*;
+ *     NULL = the default stream) and the call returns without waiting for it.
+ *   - Tensors are contiguous, innermost stride 1, in the layouts stated below.
+ *   - Every function returns a POWATTN_* status (or documents its own return
+ *     value).  Argument errors are found on the host before anything is
+ *     launched, so no kernel runs when the status is not POWATTN_OK.
+ *     Nothing aborts or throws.
+ */
+#ifndef POWATTN_H
+#define POWATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* status codes */
+#define POWATTN_OK                   0
+#define POWATTN_INVALID_ARG          1  /* null pointer, non-positive size, Hq % Hkv != 0, length > capacity ... */
+#define POWATTN_UNSUPPORTED          2  /* head_dim, block size or dtype the kernels are not built for */
+#define POWATTN_WORKSPACE_TOO_SMALL  3  /* workspace_bytes or max_k below what the call needs */
+#define POWATTN_HIP_ERROR            4  /* the HIP runtime refused a launch; see powattn_strerror */
+
+/* powattn_pattern.flags */
+#define POWATTN_POWER  1u  /* attend block distances with exactly one bit set (Algorithm 1, "mask_power") */
+#define POWATTN_DENSE  2u  /* full causal attention, A_i = {j <= i} (Section 3.1); other fields except block are ignored */
+
+/* element types of Q/K/V/O */
+#define POWATTN_BF16 0
+#define POWATTN_F32  1
+
+/*
+ * The pattern's hyper-parameters, in the notation of Algorithm 1 (Section 3.3).
+ * With blk = floor(q_idx/B) - floor(kv_idx/B), token q_idx attends token kv_idx
+ * when  q_idx >= kv_idx  and  ( blk < W  or  blk & (blk-1) == 0  or
+ * kv_idx < S*B ).  Algorithm 1 has S = 1; Section 4.1 uses B = 256, W = 5, S = 1.
+ * The power-of-two test also admits blk == 0, so with POWATTN_POWER the diagonal
+ * block is attended even when W == 0.  Without POWATTN_POWER (sliding window +
+ * sink, the first baseline of Section 4.1) W must be >= 1.
+ */
+typedef struct {
+  int32_t block;   /* B: tokens per block, >= 1 */
+  int32_t window;  /* W: block distances 0..W-1 are attended, >= 0 */
+  int32_t sink;    /* S: the first S key blocks are always attended, >= 0 */
+  uint32_t flags;  /* POWATTN_POWER | POWATTN_DENSE */
+} powattn_pattern;
+
+/* Library version: major*10000 + minor*100 + patch. */
+int powattn_version(void);
+
+/* Static, human-readable text for a status code (never NULL). For
+ * POWATTN_HIP_ERROR the text of the last HIP error seen by the calling thread
+ * is appended. */
+const char* powattn_strerror(int status);
+
+/* Number of blocks nb = ceil(seq_len / B), or -POWATTN_INVALID_ARG. */
+int64_t powattn_num_blocks(const powattn_pattern* pattern, int64_t seq_len);
+
+/*
+ * Row capacity: the largest number of key blocks any query block of a
+ * seq_len-token sequence attends (O(log nb) for the power pattern: at most
+ * W + S + the powers of two below nb; Theorem B.1 bounds the power part by
+ * log n).  Host-only.  Returns the capacity (>= 1) or -status.
+ */
+int32_t powattn_max_k(const powattn_pattern* pattern, int64_t seq_len);
+
+/*
+ * Host-side enumeration of one row of the block-sparse pattern: writes the
+ * ascending key-block indices attended by query block `q_block` to
+ * `out` (host, `capacity` entries) and returns how many there are, or -status
+ * (-POWATTN_WORKSPACE_TOO_SMALL when capacity is short; nothing is written
+ * beyond `capacity`).  `out` may be NULL with capacity 0 to query the count.
+ */
+int32_t powattn_row_host(const powattn_pattern* pattern, int64_t q_block, int32_t* out, int32_t capacity);
+
+/*
+ * Step "block-index generation" (Algorithm 1 lifted to blocks, Sections 3.3
+ * and 4.1): for each query block i in [0, nb) emit the ascending, duplicate-
+ * free list of key blocks j <= i that some token of block i attends.
+ *   d_kv_cnt     device int32 [nb]            out: list lengths
+ *   d_kv_idx     device int32 [nb, max_k]     out: lists, padded with -1
+ *   max_k        row capacity of d_kv_idx; must be >= powattn_max_k(...)
+ *   d_block_mask device uint8 [nb, nb] or NULL  out: 1 where block j is in row i
+ * Errors: INVALID_ARG (null pattern/outputs, seq_len <= 0, bad pattern),
+ * WORKSPACE_TOO_SMALL (max_k short), HIP_ERROR.
+ */
+int powattn_mask_build(const powattn_pattern* pattern, int64_t seq_len,
+                       int32_t* d_kv_cnt, int32_t* d_kv_idx, int32_t max_k,
+                       uint8_t* d_block_mask, void* hip_stream);
+
+/*
+ * Prefill: Equation 1 (Section 3.1) for every query token, with A_i given by
+ * the block lists: for query block i, every token of a listed block j < i is
+ * attended, and inside the diagonal block j == i token q attends kv <= q.
+ *   d_kv_cnt, d_kv_idx, max_k   lists as written by powattn_mask_build for the
+ *                  same pattern.block and seq_len (any causal block list is
+ *                  accepted: entries outside [0, i] are skipped).  Ignored,
+ *                  and may be NULL, when pattern->flags has POWATTN_DENSE.
+ *   q, o           device [batch, n_q_heads, seq_len, head_dim]
+ *   k, v           device [batch, n_kv_heads, seq_len, head_dim]; query head h
+ *                  reads KV head h / (n_q_heads / n_kv_heads)
+ *   lse            device float [batch, n_q_heads, seq_len] or NULL:
+ *                  natural-log sum of exp(scaled logits) over the attended keys
+ *   dtype          POWATTN_BF16 (MFMA path, fp32 accumulation; head_dim 64 or 128,
+ *                  block a multiple of 64) or POWATTN_F32 (plain FMA path;
+ *                  head_dim 64 or 128, block 16..256 and a multiple of 16)
+ *   softmax_scale  logit scale; <= 0 selects 1/sqrt(head_dim) (Equation 1)
+ * seq_len need not be a multiple of the block size.
+ * Errors: INVALID_ARG, UNSUPPORTED, HIP_ERROR.
+ */
+int powattn_prefill(const powattn_pattern* pattern,
+                    const int32_t* d_kv_cnt, const int32_t* d_kv_idx, int32_t max_k,
+                    const void* q, const void* k, const void* v, void* o, float* lse,
+                    int32_t batch, int32_t n_q_heads, int32_t n_kv_heads,
+                    int64_t seq_len, int32_t head_dim, int32_t dtype,
+                    float softmax_scale, void* hip_stream);
+
+/*
+ * Bytes of device workspace powattn_decode needs for caches of up to
+ * `cache_capacity` tokens (0 on invalid arguments).
+ */
+size_t powattn_decode_workspace_bytes(const powattn_pattern* pattern, int32_t batch,
+                                      int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                      int64_t cache_capacity);
+
+/*
+ * Decode: one new token per sequence attends its KV cache under the same
+ * pattern as prefill (Section 4.1: "consistent patterns during both prefilling
+ * and decoding").  The cache already holds the new token's key and value, so
+ * the query of sequence b sits at position t = kv_len[b] - 1 and the result
+ * equals row t of powattn_prefill over the first kv_len[b] cache positions.
+ * The attended block list of row floor(t / B) is generated inside the kernel;
+ * the work is split over the attended blocks and combined (split-K).
+ *   q, o           device [batch, n_q_heads, head_dim]
+ *   k_cache, v_cache  device [batch, n_kv_heads, cache_capacity, head_dim]
+ *   d_kv_len       device int32 [batch], 1 <= kv_len[b] <= cache_capacity
+ *                  (values outside that range are clamped into it by the kernel)
+ *   lse            device float [batch, n_q_heads] or NULL
+ *   dtype          POWATTN_BF16 only; head_dim 64 or 128; block a multiple of 64
+ *   workspace      device, at least powattn_decode_workspace_bytes(...) bytes,
+ *                  256-byte aligned; contents on entry are ignored
+ * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR.
+ */
+int powattn_decode(const powattn_pattern* pattern,
+                   const void* q, const void* k_cache, const void* v_cache,
+                   const int32_t* d_kv_len, int64_t cache_capacity,
+                   void* o, float* lse,
+                   int32_t batch, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                   int32_t dtype, float softmax_scale,
+                   void* workspace, size_t workspace_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* POWATTN_H */

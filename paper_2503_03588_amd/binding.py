@@ -1,0 +1,224 @@
+"""ctypes binding of libpowattn.so: same names as the C ABI in include/powattn.h.
+
+Only argument marshalling lives here (tensor -> pointer, current stream,
+status -> exception, output allocation through torch).  Every step of the
+attention path runs in the library's HIP kernels; if the library has not been
+built this module raises instead of computing anything itself.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpowattn.so")
+
+OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR = 0, 1, 2, 3, 4
+POWER, DENSE = 1, 2
+BF16, F32 = 0, 1
+
+EXPORTS = (
+    "powattn_version", "powattn_strerror", "powattn_num_blocks", "powattn_max_k",
+    "powattn_row_host", "powattn_mask_build", "powattn_prefill",
+    "powattn_decode_workspace_bytes", "powattn_decode",
+)
+
+
+class PowattnError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({strerror(status)})")
+
+
+class _CPattern(ctypes.Structure):
+    _fields_ = [("block", ctypes.c_int32), ("window", ctypes.c_int32),
+                ("sink", ctypes.c_int32), ("flags", ctypes.c_uint32)]
+
+
+@dataclass(frozen=True)
+class Pattern:
+    """powattn_pattern: B, W, S of Algorithm 1 plus the flag bits."""
+    block: int
+    window: int
+    sink: int = 1
+    flags: int = POWER
+
+    def c(self) -> _CPattern:
+        return _CPattern(self.block, self.window, self.sink, self.flags)
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads the built library (never builds it, never falls back)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2503_03588_amd.build` "
+            "(there is no fallback path)")
+    L = ctypes.CDLL(LIB_PATH)
+    P = ctypes.POINTER(_CPattern)
+    vp, i32, i64, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+    L.powattn_version.restype = ctypes.c_int
+    L.powattn_version.argtypes = []
+    L.powattn_strerror.restype = ctypes.c_char_p
+    L.powattn_strerror.argtypes = [ctypes.c_int]
+    L.powattn_num_blocks.restype = i64
+    L.powattn_num_blocks.argtypes = [P, i64]
+    L.powattn_max_k.restype = i32
+    L.powattn_max_k.argtypes = [P, i64]
+    L.powattn_row_host.restype = i32
+    L.powattn_row_host.argtypes = [P, i64, ctypes.POINTER(i32), i32]
+    L.powattn_mask_build.restype = ctypes.c_int
+    L.powattn_mask_build.argtypes = [P, i64, vp, vp, i32, vp, vp]
+    L.powattn_prefill.restype = ctypes.c_int
+    L.powattn_prefill.argtypes = [P, vp, vp, i32, vp, vp, vp, vp, vp, i32, i32, i32, i64, i32, i32, f32, vp]
+    L.powattn_decode_workspace_bytes.restype = ctypes.c_size_t
+    L.powattn_decode_workspace_bytes.argtypes = [P, i32, i32, i32, i32, i64]
+    L.powattn_decode.restype = ctypes.c_int
+    L.powattn_decode.argtypes = [P, vp, vp, vp, vp, i64, vp, vp, i32, i32, i32, i32, i32, f32,
+                                 vp, ctypes.c_size_t, vp]
+    _lib = L
+    return L
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(stream=None):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return BF16
+    if t.dtype == torch.float32:
+        return F32
+    raise ValueError(f"unsupported dtype {t.dtype}")
+
+
+def _check(status: int, where: str):
+    if status != OK:
+        raise PowattnError(status, where)
+
+
+# ---- host-only queries --------------------------------------------------------
+def version() -> int:
+    return lib().powattn_version()
+
+
+def strerror(status: int) -> str:
+    return lib().powattn_strerror(status).decode()
+
+
+def num_blocks(pattern: Pattern, seq_len: int) -> int:
+    n = lib().powattn_num_blocks(ctypes.byref(pattern.c()), seq_len)
+    if n < 0:
+        raise PowattnError(-n, "powattn_num_blocks")
+    return n
+
+
+def max_k(pattern: Pattern, seq_len: int) -> int:
+    n = lib().powattn_max_k(ctypes.byref(pattern.c()), seq_len)
+    if n < 0:
+        raise PowattnError(-n, "powattn_max_k")
+    return n
+
+
+def row_host(pattern: Pattern, q_block: int):
+    L = lib()
+    cp = pattern.c()
+    n = L.powattn_row_host(ctypes.byref(cp), q_block, None, 0)
+    if n < 0:
+        raise PowattnError(-n, "powattn_row_host")
+    buf = (ctypes.c_int32 * max(n, 1))()
+    n2 = L.powattn_row_host(ctypes.byref(cp), q_block, buf, n)
+    if n2 < 0:
+        raise PowattnError(-n2, "powattn_row_host")
+    return list(buf[:n2])
+
+
+def decode_workspace_bytes(pattern: Pattern, batch, n_q_heads, n_kv_heads, head_dim, cache_capacity) -> int:
+    return lib().powattn_decode_workspace_bytes(ctypes.byref(pattern.c()), batch, n_q_heads, n_kv_heads,
+                                                head_dim, cache_capacity)
+
+
+# ---- device entry points ---------------------------------------------------------
+def mask_build(pattern: Pattern, seq_len: int, kv_cnt=None, kv_idx=None, block_mask=None,
+               want_block_mask=False, device="cuda", stream=None):
+    """powattn_mask_build.  Allocates the outputs when they are not given.
+    Returns (kv_cnt int32 [nb], kv_idx int32 [nb, max_k], block_mask uint8 [nb, nb] or None)."""
+    nb = num_blocks(pattern, seq_len)
+    if kv_idx is None:
+        mk = max_k(pattern, seq_len)
+        kv_idx = torch.empty((nb, mk), dtype=torch.int32, device=device)
+    if kv_cnt is None:
+        kv_cnt = torch.empty((nb,), dtype=torch.int32, device=device)
+    if block_mask is None and want_block_mask:
+        block_mask = torch.empty((nb, nb), dtype=torch.uint8, device=device)
+    st = lib().powattn_mask_build(ctypes.byref(pattern.c()), seq_len, _ptr(kv_cnt), _ptr(kv_idx),
+                                  kv_idx.shape[1], _ptr(block_mask), _stream(stream))
+    _check(st, "powattn_mask_build")
+    return kv_cnt, kv_idx, block_mask
+
+
+def prefill(pattern: Pattern, kv_cnt, kv_idx, q, k, v, o=None, lse=None, softmax_scale=0.0,
+            want_lse=True, stream=None):
+    """powattn_prefill.  q/o: [b,Hq,N,D]; k/v: [b,Hkv,N,D].  Returns (o, lse)."""
+    batch, hq, n, d = q.shape
+    hkv = k.shape[1]
+    if k.shape != (batch, hkv, n, d) or v.shape != k.shape:
+        raise ValueError("k/v shape mismatch")
+    if k.dtype != q.dtype or v.dtype != q.dtype:
+        raise ValueError("q/k/v dtype mismatch")
+    if o is None:
+        o = torch.empty_like(q)
+    if lse is None and want_lse:
+        lse = torch.empty((batch, hq, n), dtype=torch.float32, device=q.device)
+    mk = kv_idx.shape[1] if kv_idx is not None else 0
+    if kv_idx is not None and kv_cnt.shape[0] * pattern.block < n:
+        raise ValueError("block lists shorter than the sequence")
+    st = lib().powattn_prefill(ctypes.byref(pattern.c()), _ptr(kv_cnt), _ptr(kv_idx), mk,
+                               _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse),
+                               batch, hq, hkv, n, d, _dtype_code(q), float(softmax_scale), _stream(stream))
+    _check(st, "powattn_prefill")
+    return o, lse
+
+
+def decode(pattern: Pattern, q, k_cache, v_cache, kv_len, o=None, lse=None, softmax_scale=0.0,
+           workspace=None, want_lse=True, stream=None):
+    """powattn_decode.  q/o: [b,Hq,D]; caches: [b,Hkv,capacity,D]; kv_len int32 [b].  Returns (o, lse)."""
+    batch, hq, d = q.shape
+    hkv, cap = k_cache.shape[1], k_cache.shape[2]
+    if k_cache.shape != (batch, hkv, cap, d) or v_cache.shape != k_cache.shape:
+        raise ValueError("cache shape mismatch")
+    if kv_len.dtype != torch.int32 or kv_len.shape != (batch,):
+        raise ValueError("kv_len must be int32 [batch]")
+    if o is None:
+        o = torch.empty_like(q)
+    if lse is None and want_lse:
+        lse = torch.empty((batch, hq), dtype=torch.float32, device=q.device)
+    if workspace is None:
+        need = decode_workspace_bytes(pattern, batch, hq, hkv, d, cap)
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=q.device)
+    st = lib().powattn_decode(ctypes.byref(pattern.c()), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(kv_len),
+                              cap, _ptr(o), _ptr(lse), batch, hq, hkv, d, _dtype_code(q),
+                              float(softmax_scale), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                              _stream(stream))
+    _check(st, "powattn_decode")
+    return o, lse

@@ -1,0 +1,156 @@
+// Host side of the C ABI: argument checks, host-only queries, dispatch.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+#include "common.h"
+
+static thread_local char g_hip_msg[256] = "";
+static thread_local char g_msg_buf[384];
+
+int pa_note_hip(hipError_t e) {
+  if (e == hipSuccess) return POWATTN_OK;
+  snprintf(g_hip_msg, sizeof(g_hip_msg), "%s", hipGetErrorString(e));
+  return POWATTN_HIP_ERROR;
+}
+
+int pa_check_pattern(const powattn_pattern* p) {
+  if (!p) return POWATTN_INVALID_ARG;
+  if (p->block < 1 || p->window < 0 || p->sink < 0) return POWATTN_INVALID_ARG;
+  if (p->flags & ~(POWATTN_POWER | POWATTN_DENSE)) return POWATTN_INVALID_ARG;
+  // without the power term nothing guarantees the diagonal block: need a window
+  if (!(p->flags & (POWATTN_POWER | POWATTN_DENSE)) && p->window < 1) return POWATTN_INVALID_ARG;
+  return POWATTN_OK;
+}
+
+extern "C" int powattn_version(void) { return POWATTN_VERSION_NUMBER; }
+
+extern "C" const char* powattn_strerror(int status) {
+  switch (status) {
+    case POWATTN_OK: return "ok";
+    case POWATTN_INVALID_ARG: return "invalid argument";
+    case POWATTN_UNSUPPORTED: return "unsupported head_dim, block size or dtype";
+    case POWATTN_WORKSPACE_TOO_SMALL: return "workspace or max_k too small";
+    case POWATTN_HIP_ERROR:
+      snprintf(g_msg_buf, sizeof(g_msg_buf), "HIP error: %s", g_hip_msg[0] ? g_hip_msg : "(none recorded)");
+      return g_msg_buf;
+    default: return "unknown status";
+  }
+}
+
+extern "C" int64_t powattn_num_blocks(const powattn_pattern* p, int64_t seq_len) {
+  if (pa_check_pattern(p) != POWATTN_OK || seq_len <= 0) return -POWATTN_INVALID_ARG;
+  int64_t nb = (seq_len + p->block - 1) / p->block;
+  if (nb > INT32_MAX) return -POWATTN_INVALID_ARG;
+  return nb;
+}
+
+extern "C" int32_t powattn_row_host(const powattn_pattern* p, int64_t q_block, int32_t* out, int32_t capacity) {
+  if (pa_check_pattern(p) != POWATTN_OK || q_block < 0 || q_block > INT32_MAX || capacity < 0) return -POWATTN_INVALID_ARG;
+  if (!out && capacity != 0) return -POWATTN_INVALID_ARG;
+  int64_t n = pa_for_each_block(p->window, p->sink, p->flags, q_block, [](int64_t) {});
+  if (!out) return (int32_t)n;
+  if (n > capacity) return -POWATTN_WORKSPACE_TOO_SMALL;
+  int32_t w = 0;
+  pa_for_each_block(p->window, p->sink, p->flags, q_block, [&](int64_t j) { out[w++] = (int32_t)j; });
+  return w;
+}
+
+extern "C" int32_t powattn_max_k(const powattn_pattern* p, int64_t seq_len) {
+  int64_t nb = powattn_num_blocks(p, seq_len);
+  if (nb < 0) return (int32_t)nb;
+  if (p->flags & POWATTN_DENSE) return (int32_t)nb;
+  int64_t best = 0;
+  for (int64_t i = 0; i < nb; ++i) {
+    int64_t n = pa_for_each_block(p->window, p->sink, p->flags, i, [](int64_t) {});
+    if (n > best) best = n;
+  }
+  return (int32_t)best;
+}
+
+static bool supported_head_dim(int32_t d) { return d == 64 || d == 128; }
+
+extern "C" int powattn_prefill(const powattn_pattern* pattern,
+                               const int32_t* d_kv_cnt, const int32_t* d_kv_idx, int32_t max_k,
+                               const void* q, const void* k, const void* v, void* o, float* lse,
+                               int32_t batch, int32_t n_q_heads, int32_t n_kv_heads,
+                               int64_t seq_len, int32_t head_dim, int32_t dtype,
+                               float softmax_scale, void* hip_stream) {
+  int st = pa_check_pattern(pattern);
+  if (st != POWATTN_OK) return st;
+  if (!q || !k || !v || !o) return POWATTN_INVALID_ARG;
+  if (batch < 1 || n_q_heads < 1 || n_kv_heads < 1 || seq_len < 1 || head_dim < 1) return POWATTN_INVALID_ARG;
+  if (n_q_heads % n_kv_heads != 0) return POWATTN_INVALID_ARG;
+  const bool dense = (pattern->flags & POWATTN_DENSE) != 0;
+  if (!dense && (!d_kv_cnt || !d_kv_idx || max_k < 1)) return POWATTN_INVALID_ARG;
+  int64_t nb = powattn_num_blocks(pattern, seq_len);
+  if (nb < 0) return POWATTN_INVALID_ARG;
+  if (!(softmax_scale == softmax_scale)) return POWATTN_INVALID_ARG;  // NaN
+  if (dtype != POWATTN_BF16 && dtype != POWATTN_F32) return POWATTN_UNSUPPORTED;
+  if (!supported_head_dim(head_dim)) return POWATTN_UNSUPPORTED;
+  if ((int64_t)batch * n_q_heads > 65535 * 16) return POWATTN_UNSUPPORTED;
+
+  pa_prefill_args a;
+  a.pat = *pattern;
+  a.kv_cnt = d_kv_cnt; a.kv_idx = d_kv_idx; a.max_k = max_k;
+  a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
+  a.batch = batch; a.hq = n_q_heads; a.hkv = n_kv_heads;
+  a.seq_len = seq_len; a.nb = (int32_t)nb; a.head_dim = head_dim;
+  a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)head_dim);
+  a.stream = (hipStream_t)hip_stream;
+  if (dtype == POWATTN_F32) {
+    const int32_t B = pattern->block;
+    if (B < 16 || B > 256 || B % 16 != 0) return POWATTN_UNSUPPORTED;
+    return pa_launch_prefill_f32(a);
+  }
+  if (pattern->block % 64 != 0 || pattern->block > 1024) return POWATTN_UNSUPPORTED;
+  return pa_launch_prefill_bf16(a);
+}
+
+extern "C" size_t powattn_decode_workspace_bytes(const powattn_pattern* pattern, int32_t batch,
+                                                 int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                                 int64_t cache_capacity) {
+  if (pa_check_pattern(pattern) != POWATTN_OK) return 0;
+  if (batch < 1 || n_q_heads < 1 || n_kv_heads < 1 || head_dim < 1 || cache_capacity < 1) return 0;
+  if (n_q_heads % n_kv_heads != 0) return 0;
+  int32_t ns = pa_decode_splits(pattern, cache_capacity);
+  if (ns < 1) return 0;
+  // per (batch, q head, split): head_dim partial outputs + running max + running sum
+  size_t partials = (size_t)batch * n_q_heads * ns * (size_t)(head_dim + 2) * sizeof(float);
+  return (partials + 255) & ~(size_t)255;
+}
+
+extern "C" int powattn_decode(const powattn_pattern* pattern,
+                              const void* q, const void* k_cache, const void* v_cache,
+                              const int32_t* d_kv_len, int64_t cache_capacity,
+                              void* o, float* lse,
+                              int32_t batch, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                              int32_t dtype, float softmax_scale,
+                              void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int st = pa_check_pattern(pattern);
+  if (st != POWATTN_OK) return st;
+  if (!q || !k_cache || !v_cache || !d_kv_len || !o) return POWATTN_INVALID_ARG;
+  if (batch < 1 || n_q_heads < 1 || n_kv_heads < 1 || head_dim < 1 || cache_capacity < 1) return POWATTN_INVALID_ARG;
+  if (n_q_heads % n_kv_heads != 0) return POWATTN_INVALID_ARG;
+  if (!(softmax_scale == softmax_scale)) return POWATTN_INVALID_ARG;
+  if (dtype != POWATTN_BF16) return POWATTN_UNSUPPORTED;
+  if (!supported_head_dim(head_dim)) return POWATTN_UNSUPPORTED;
+  if (pattern->block % 64 != 0 || pattern->block > 1024) return POWATTN_UNSUPPORTED;
+  if (pattern->flags & POWATTN_DENSE) return POWATTN_UNSUPPORTED;
+  if (n_q_heads / n_kv_heads > 16) return POWATTN_UNSUPPORTED;
+  if (powattn_num_blocks(pattern, cache_capacity) < 0) return POWATTN_INVALID_ARG;
+  size_t need = powattn_decode_workspace_bytes(pattern, batch, n_q_heads, n_kv_heads, head_dim, cache_capacity);
+  if (need == 0) return POWATTN_INVALID_ARG;
+  if (!workspace || workspace_bytes < need) return POWATTN_WORKSPACE_TOO_SMALL;
+  if (((uintptr_t)workspace & 255u) != 0) return POWATTN_INVALID_ARG;
+
+  pa_decode_args a;
+  a.pat = *pattern;
+  a.q = q; a.k = k_cache; a.v = v_cache; a.kv_len = d_kv_len; a.capacity = cache_capacity;
+  a.o = o; a.lse = lse;
+  a.batch = batch; a.hq = n_q_heads; a.hkv = n_kv_heads; a.head_dim = head_dim;
+  a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)head_dim);
+  a.workspace = workspace;
+  a.n_split = pa_decode_splits(pattern, cache_capacity);
+  a.stream = (hipStream_t)hip_stream;
+  return pa_launch_decode_bf16(a);
+}

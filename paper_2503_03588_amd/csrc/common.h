@@ -1,0 +1,44 @@
+// Shared host-side declarations of the library's translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/powattn.h"
+#include "pattern.h"
+
+#define POWATTN_VERSION_NUMBER 100  // 0.1.0
+
+// Records a HIP error for powattn_strerror and maps it to a status.
+int pa_note_hip(hipError_t e);
+int pa_check_pattern(const powattn_pattern* p);
+
+struct pa_prefill_args {
+  powattn_pattern pat;
+  const int32_t* kv_cnt;
+  const int32_t* kv_idx;
+  int32_t max_k;
+  const void* q; const void* k; const void* v; void* o; float* lse;
+  int32_t batch, hq, hkv;
+  int64_t seq_len;
+  int32_t nb;      // ceil(seq_len / block)
+  int32_t head_dim;
+  float scale;     // softmax scale (natural units)
+  hipStream_t stream;
+};
+
+int pa_launch_prefill_f32(const pa_prefill_args& a);
+int pa_launch_prefill_bf16(const pa_prefill_args& a);
+
+struct pa_decode_args {
+  powattn_pattern pat;
+  const void* q; const void* k; const void* v;
+  const int32_t* kv_len;
+  int64_t capacity;
+  void* o; float* lse;
+  int32_t batch, hq, hkv, head_dim;
+  float scale;
+  void* workspace;
+  int32_t n_split;   // partial slots per (batch, kv head)
+  hipStream_t stream;
+};
+int pa_launch_decode_bf16(const pa_decode_args& a);
+int32_t pa_decode_splits(const powattn_pattern* pat, int64_t capacity);

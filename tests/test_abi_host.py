@@ -1,0 +1,149 @@
+"""Host-only checks of the C ABI: the library loads, exports every function the
+header declares, answers the host-side queries like the oracle does, and turns
+bad arguments into status codes before anything could be launched (CPU only:
+no call here reaches a kernel launch)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import powattn_oracle as orc
+from paper_2503_03588_amd import binding as pa
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000          # a non-null "device pointer" that is never dereferenced on these paths
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(pa.LIB_PATH):
+        pytest.fail("libpowattn.so has not been built (python -m paper_2503_03588_amd.build)")
+    return pa.lib()
+
+
+def test_every_declared_function_is_exported(L):
+    text = open(os.path.join(ROOT, "include", "powattn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(powattn_[a-z_0-9]+)\s*\(", text))
+    assert declared == set(pa.EXPORTS)
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_version_and_strerror(L):
+    assert pa.version() >= 100
+    assert pa.strerror(pa.OK) == "ok"
+    for st in (pa.INVALID_ARG, pa.UNSUPPORTED, pa.WORKSPACE_TOO_SMALL, pa.HIP_ERROR, 77):
+        assert isinstance(pa.strerror(st), str) and pa.strerror(st)
+
+
+@pytest.mark.parametrize("n,B,W,S,flags", [
+    (1024, 64, 2, 1, pa.POWER), (1024, 64, 2, 0, pa.POWER), (32768, 64, 4, 1, pa.POWER),
+    (131072, 128, 4, 1, pa.POWER), (32768, 256, 5, 1, pa.POWER), (32768, 256, 9, 1, 0),
+    (1000, 64, 0, 0, pa.POWER), (5000, 16, 3, 5, pa.POWER), (777, 16, 2, 1, pa.DENSE),
+])
+def test_host_rows_and_capacity_match_oracle(L, n, B, W, S, flags):
+    pat = pa.Pattern(B, W, S, flags)
+    opat = orc.Pattern(B, W, S, power=bool(flags & pa.POWER), dense=bool(flags & pa.DENSE))
+    cnt, idx, mk = orc.block_lists(n, opat)
+    assert pa.num_blocks(pat, n) == cnt.shape[0]
+    assert pa.max_k(pat, n) == mk
+    for i in sorted(set([0, 1, 2, 3, cnt.shape[0] // 2, cnt.shape[0] - 2, cnt.shape[0] - 1])):
+        if 0 <= i < cnt.shape[0]:
+            assert pa.row_host(pat, i) == idx[i, : cnt[i]].tolist()
+
+
+def test_row_host_capacity_error(L):
+    cp = pa.Pattern(64, 4, 1).c()
+    buf = (ctypes.c_int32 * 4)()
+    assert L.powattn_row_host(ctypes.byref(cp), 1023, buf, 4) == -pa.WORKSPACE_TOO_SMALL
+    assert L.powattn_row_host(ctypes.byref(cp), -1, buf, 4) == -pa.INVALID_ARG
+    assert L.powattn_row_host(None, 3, buf, 4) == -pa.INVALID_ARG
+
+
+def test_bad_patterns(L):
+    for pat in (pa.Pattern(0, 2, 1), pa.Pattern(64, -1, 1), pa.Pattern(64, 2, -1),
+                pa.Pattern(64, 2, 1, flags=8), pa.Pattern(64, 0, 1, flags=0)):
+        cp = pat.c()
+        assert L.powattn_max_k(ctypes.byref(cp), 1024) == -pa.INVALID_ARG
+        assert L.powattn_mask_build(ctypes.byref(cp), 1024, FAKE, FAKE, 16, None, None) == pa.INVALID_ARG
+    cp = pa.Pattern(64, 2, 1).c()
+    assert L.powattn_num_blocks(ctypes.byref(cp), 0) == -pa.INVALID_ARG
+
+
+def test_mask_build_argument_errors(L):
+    cp = pa.Pattern(64, 4, 1).c()
+    assert L.powattn_mask_build(None, 1024, FAKE, FAKE, 16, None, None) == pa.INVALID_ARG
+    assert L.powattn_mask_build(ctypes.byref(cp), 1024, None, FAKE, 16, None, None) == pa.INVALID_ARG
+    assert L.powattn_mask_build(ctypes.byref(cp), 1024, FAKE, None, 16, None, None) == pa.INVALID_ARG
+    assert L.powattn_mask_build(ctypes.byref(cp), -5, FAKE, FAKE, 16, None, None) == pa.INVALID_ARG
+    assert L.powattn_mask_build(ctypes.byref(cp), 65536, FAKE, FAKE, 12, None, None) == pa.WORKSPACE_TOO_SMALL
+
+
+def _prefill(L, pat=None, cnt=FAKE, idx=FAKE, max_k=13, q=FAKE, k=FAKE, v=FAKE, o=FAKE, lse=None,
+             batch=1, hq=4, hkv=2, n=1024, d=128, dtype=pa.BF16, scale=0.0):
+    cp = (pat or pa.Pattern(64, 4, 1)).c()
+    return L.powattn_prefill(ctypes.byref(cp), cnt, idx, max_k, q, k, v, o, lse, batch, hq, hkv, n, d, dtype,
+                             scale, None)
+
+
+def test_prefill_argument_errors(L):
+    assert _prefill(L, q=None) == pa.INVALID_ARG
+    assert _prefill(L, k=None) == pa.INVALID_ARG
+    assert _prefill(L, v=None) == pa.INVALID_ARG
+    assert _prefill(L, o=None) == pa.INVALID_ARG
+    assert _prefill(L, cnt=None) == pa.INVALID_ARG
+    assert _prefill(L, idx=None) == pa.INVALID_ARG
+    assert _prefill(L, max_k=0) == pa.INVALID_ARG
+    assert _prefill(L, hq=6, hkv=4) == pa.INVALID_ARG
+    assert _prefill(L, batch=0) == pa.INVALID_ARG
+    assert _prefill(L, n=0) == pa.INVALID_ARG
+    assert _prefill(L, scale=float("nan")) == pa.INVALID_ARG
+    assert _prefill(L, d=96) == pa.UNSUPPORTED
+    assert _prefill(L, dtype=5) == pa.UNSUPPORTED
+    assert _prefill(L, pat=pa.Pattern(48, 4, 1)) == pa.UNSUPPORTED            # bf16 needs a multiple of 64
+    assert _prefill(L, pat=pa.Pattern(24, 4, 1), dtype=pa.F32) == pa.UNSUPPORTED
+
+
+def _decode(L, pat=None, q=FAKE, k=FAKE, v=FAKE, kv_len=FAKE, cap=65536, o=FAKE, lse=None, batch=2, hq=8,
+            hkv=2, d=128, dtype=pa.BF16, scale=0.0, ws=FAKE, ws_bytes=None):
+    p = pat or pa.Pattern(64, 4, 1)
+    cp = p.c()
+    if ws_bytes is None:
+        ws_bytes = L.powattn_decode_workspace_bytes(ctypes.byref(cp), batch, hq, hkv, d, cap)
+    return L.powattn_decode(ctypes.byref(cp), q, k, v, kv_len, cap, o, lse, batch, hq, hkv, d, dtype, scale,
+                            ws, ws_bytes, None)
+
+
+def test_decode_argument_errors(L):
+    assert _decode(L, q=None) == pa.INVALID_ARG
+    assert _decode(L, k=None) == pa.INVALID_ARG
+    assert _decode(L, v=None) == pa.INVALID_ARG
+    assert _decode(L, kv_len=None) == pa.INVALID_ARG
+    assert _decode(L, o=None) == pa.INVALID_ARG
+    assert _decode(L, cap=0) == pa.INVALID_ARG
+    assert _decode(L, hq=6, hkv=4) == pa.INVALID_ARG
+    assert _decode(L, d=80) == pa.UNSUPPORTED
+    assert _decode(L, dtype=pa.F32) == pa.UNSUPPORTED
+    assert _decode(L, pat=pa.Pattern(32, 4, 1)) == pa.UNSUPPORTED
+    assert _decode(L, ws=None) == pa.WORKSPACE_TOO_SMALL
+    assert _decode(L, ws_bytes=64) == pa.WORKSPACE_TOO_SMALL
+    assert _decode(L, ws=FAKE + 8) == pa.INVALID_ARG                          # misaligned workspace
+
+
+def test_decode_workspace_size(L):
+    pat = pa.Pattern(64, 4, 1)
+    n = pa.decode_workspace_bytes(pat, 16, 32, 8, 128, 65536)
+    assert n > 0 and n % 256 == 0
+    assert pa.decode_workspace_bytes(pat, 16, 32, 8, 128, 131072) >= n
+    assert pa.decode_workspace_bytes(pat, 0, 32, 8, 128, 65536) == 0
+    assert pa.decode_workspace_bytes(pat, 16, 30, 8, 128, 65536) == 0
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(pa, "_lib", None)
+    monkeypatch.setattr(pa, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(RuntimeError, match="no fallback"):
+        pa.version()

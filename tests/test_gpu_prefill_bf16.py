@@ -1,0 +1,107 @@
+"""GPU parity: bf16 powattn_prefill (MFMA path) vs the float64 oracle.
+Bar: max abs error 2e-2 on the outputs, 1e-3 on the log-sum-exp."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2503_03588_amd import binding as pa
+from paper_2503_03588_amd import synth
+from gpu_util import check_prefill, gpu_prefill, sample_rows
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("n,B,W,S,hq,hkv,d,batch", [
+    (2048, 64, 4, 1, 4, 1, 128, 1),     # config-2 shape family, GQA 4
+    (2048, 64, 4, 0, 4, 1, 128, 1),     # no sink
+    (4096, 128, 4, 1, 8, 2, 128, 1),    # config-3 shape family: two 64-key tiles per block
+    (3072, 64, 4, 1, 7, 1, 128, 1),     # config-5 shape family: GQA 7 (one idle wavefront)
+    (1000, 64, 2, 1, 2, 2, 128, 1),     # ragged tail, no GQA
+    (1500, 128, 2, 1, 4, 2, 64, 2),     # head_dim 64, batch 2, ragged
+    (2048, 256, 5, 1, 4, 2, 128, 1),    # the paper's block size and window (Section 4.1)
+    (50, 64, 4, 1, 2, 1, 128, 1),       # shorter than one block
+    (1024, 64, 0, 0, 4, 4, 128, 1),     # W = 0: pure power pattern
+    (2048, 64, 4, 1, 16, 1, 64, 1),     # 16 heads per KV head: several workgroups per query block
+])
+def test_shapes(n, B, W, S, hq, hkv, d, batch):
+    check_prefill(pa.Pattern(B, W, S), batch, hq, hkv, n, d, "bf16", seed=21)
+
+
+def test_sliding_window_and_dense_flags():
+    check_prefill(pa.Pattern(64, 3, 1, flags=0), 1, 4, 2, 2048, 128, "bf16", seed=22)
+    check_prefill(pa.Pattern(64, 3, 1, flags=pa.DENSE), 1, 4, 2, 2048, 128, "bf16", seed=23)
+    check_prefill(pa.Pattern(128, 3, 1, flags=pa.DENSE), 1, 2, 1, 1111, 64, "bf16", seed=24)
+
+
+def test_explicit_scale_and_small_std():
+    check_prefill(pa.Pattern(64, 2, 1), 1, 4, 2, 1024, 128, "bf16", seed=25, scale=0.2)
+    # the other reading of "N(0,1) scaled by 1/sqrt(128)": inputs themselves scaled
+    check_prefill(pa.Pattern(64, 4, 1), 1, 4, 1, 2048, 128, "bf16", seed=26, std=1.0 / math.sqrt(128))
+
+
+def test_window_covering_everything_equals_dense_kernel():
+    q, k, v = synth.qkv(1, 4, 2, 2048, 128, "bf16", seed=27)
+    o1, l1 = gpu_prefill(pa.Pattern(64, 32, 1), q, k, v)
+    o2, l2 = gpu_prefill(pa.Pattern(64, 1, 0, flags=pa.DENSE), q, k, v)
+    assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
+
+
+def test_zero_keys_closed_form_pins_the_mask_through_the_kernel():
+    n, B, W, S, d = 4096, 128, 2, 1, 128
+    q, _, v = synth.qkv(1, 2, 1, n, d, "bf16", seed=28)
+    k = torch.zeros_like(v)
+    o, lse = gpu_prefill(pa.Pattern(B, W, S), q, k, v)
+    vv = v[0, 0].double().numpy()
+    for i in (0, 1, 63, 64, 127, 128, 200, 1023, 1024, 2500, 4095):
+        bi = i // B
+        js = [j for j in range(i + 1) if (bi - j // B) < W or j // B < S or bin(bi - j // B).count("1") <= 1]
+        assert abs(lse[0, 0, i] - math.log(len(js))) < 1e-4
+        assert np.abs(o[0, 0, i] - vv[js].mean(axis=0)).max() < 1e-2
+
+
+def test_custom_block_lists_are_honoured():
+    # a hand-made causal list (stride pattern) with padding, a duplicate-free unsorted row and junk entries
+    n, B, d = 1024, 64, 128
+    nb = n // B
+    rows = []
+    for i in range(nb):
+        js = sorted(set([i, max(i - 1, 0)] + list(range(0, i + 1, 5))))
+        rows.append(js)
+    mk = max(len(r) for r in rows) + 2
+    idx = np.full((nb, mk), -1, dtype=np.int32)
+    cnt = np.zeros(nb, dtype=np.int32)
+    for i, js in enumerate(rows):
+        idx[i, 1:1 + len(js)] = js[::-1]          # descending order, shifted by a pad entry
+        idx[i, 0] = nb + 7                        # junk: beyond the diagonal, must be skipped
+        cnt[i] = len(js) + 1
+    q, k, v = synth.qkv(1, 2, 1, n, d, "bf16", seed=29)
+    pat = pa.Pattern(B, 1, 0)
+    o, lse = gpu_prefill(pat, q, k, v, lists=(torch.from_numpy(cnt).cuda(), torch.from_numpy(idx).cuda()))
+    # oracle: dense mask built from the same rows
+    from oracle import powattn_oracle as orc
+    qs, ks, vs = (orc.widen(synth.to_numpy_storage(t)) for t in (q, k, v))
+    allowed = np.zeros((n, n), dtype=bool)
+    for i, js in enumerate(rows):
+        for j in js:
+            allowed[i * B:(i + 1) * B, j * B:(j + 1) * B] = True
+    allowed &= np.tril(np.ones((n, n), dtype=bool))
+    for h in range(2):
+        s = (qs[0, h] @ ks[0, 0].T) / math.sqrt(d)
+        oo, ol = orc._softmax_rows(s, allowed, vs[0, 0])
+        assert np.abs(o[0, h] - oo).max() < 2e-2 and np.abs(lse[0, h] - ol).max() < 1e-3
+
+
+@pytest.mark.parametrize("cfg", [
+    # name, batch, hq, hkv, n, d, B, W : BASELINE configurations 2, 3 and one layer of 5 at full size
+    ("prefill_32k", 1, 32, 8, 32768, 128, 64, 4),
+    ("long_128k", 1, 32, 8, 131072, 128, 128, 4),
+    ("stack_64k", 1, 28, 4, 65536, 128, 64, 4),
+])
+def test_full_size_sampled_rows(cfg):
+    name, batch, hq, hkv, n, d, B, W = cfg
+    seed = {"prefill_32k": 1, "long_128k": 2, "stack_64k": 4000}[name]
+    # 7 characteristic query blocks in full + 64 random rows, every head, against all N keys
+    rows = sample_rows(n, B, W, 64, seed)
+    check_prefill(pa.Pattern(B, W, 1), batch, hq, hkv, n, d, "bf16", seed=seed, rows=rows)

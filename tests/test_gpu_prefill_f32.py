@@ -1,0 +1,61 @@
+"""GPU parity: fp32 powattn_prefill vs the float64 oracle, element by element.
+Bar: max abs error 1e-5 on the outputs, 1e-3 on the log-sum-exp."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2503_03588_amd import binding as pa
+from paper_2503_03588_amd import synth
+from gpu_util import check_prefill, gpu_prefill
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("sink", [1, 0])
+def test_config1_tiny_prefill(sink):
+    # batch 1, 2 heads, seq 1024, head_dim 64, block 64, window 2, fp32 N(0,1), seed 0
+    check_prefill(pa.Pattern(64, 2, sink), 1, 2, 2, 1024, 64, "f32", seed=0)
+
+
+@pytest.mark.parametrize("n,B,W,S,hq,hkv,d,batch", [
+    (1000, 64, 2, 1, 2, 2, 64, 1),      # ragged tail
+    (300, 16, 2, 1, 2, 1, 64, 2),       # small blocks, GQA, batch
+    (777, 32, 3, 2, 4, 2, 128, 1),      # 32-token blocks, head_dim 128
+    (2048, 128, 4, 1, 8, 2, 128, 1),    # two key tiles per block
+    (1536, 256, 1, 0, 3, 3, 64, 1),     # four key tiles per block, pure power pattern
+    (50, 64, 4, 1, 2, 2, 64, 1),        # shorter than one block
+    (1024, 64, 0, 0, 2, 2, 64, 1),      # W = 0
+])
+def test_shapes(n, B, W, S, hq, hkv, d, batch):
+    check_prefill(pa.Pattern(B, W, S), batch, hq, hkv, n, d, "f32", seed=11)
+
+
+def test_sliding_window_and_dense_flags():
+    check_prefill(pa.Pattern(64, 3, 1, flags=0), 1, 2, 1, 1024, 64, "f32", seed=12)
+    check_prefill(pa.Pattern(64, 3, 1, flags=pa.DENSE), 1, 2, 1, 1024, 64, "f32", seed=13)
+
+
+def test_explicit_scale():
+    check_prefill(pa.Pattern(64, 2, 1), 1, 2, 2, 512, 64, "f32", seed=14, scale=0.05)
+
+
+def test_window_covering_everything_equals_dense_kernel():
+    q, k, v = synth.qkv(1, 4, 2, 1024, 64, "f32", seed=15)
+    o1, l1 = gpu_prefill(pa.Pattern(64, 16, 1), q, k, v)
+    o2, l2 = gpu_prefill(pa.Pattern(64, 1, 0, flags=pa.DENSE), q, k, v)
+    assert np.abs(o1 - o2).max() < 1e-6 and np.abs(l1 - l2).max() < 1e-5
+
+
+def test_zero_keys_closed_form_pins_the_mask_through_the_kernel():
+    n, B, W, S, d = 1024, 64, 2, 1, 64
+    q, _, v = synth.qkv(1, 1, 1, n, d, "f32", seed=16)
+    k = torch.zeros_like(v)
+    o, lse = gpu_prefill(pa.Pattern(B, W, S), q, k, v)
+    vv = v[0, 0].double().numpy()
+    for i in (0, 1, 63, 64, 200, 511, 512, 1000, 1023):
+        bi = i // B
+        js = [j for j in range(i + 1) if (bi - j // B) < W or j // B < S or bin(bi - j // B).count("1") <= 1]
+        assert abs(lse[0, 0, i] - math.log(len(js))) < 1e-5
+        assert np.abs(o[0, 0, i] - vv[js].mean(axis=0)).max() < 1e-5
