@@ -1,0 +1,205 @@
+#!/usr/bin/env python3
+"""Benchmark of the PowerAttention hot path on one MI355X.
+
+One "step" = one pass of the method's path over one batch of synthetic input:
+  block-index generation (powattn_mask_build)
+  + sparse prefill at 128K context (BASELINE configuration 3: batch 1, 32 query / 8 KV heads,
+    head_dim 128, seq 131072, block 128, window 4, sink 1, bf16 N(0,1))
+  + one decode step (BASELINE configuration 4: batch 16, 32/8 heads, 65536-token bf16 caches,
+    block 64, window 4, sink 1), rotating over several distinct caches so the reads come from HBM.
+The in-library dense causal kernel (the comparison leg) and the CPU oracle are timed outside
+the timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--no-dense]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
+PEAK_HBM_GBS = 8000.0            # MI355X HBM3E peak
+
+# HBM traffic of one prefill launch at the default workload, from rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE runs scaled by a copy kernel of known size (profiles/prefill_bf16_128k_pmc.md).
+# None until measured for the current kernel.
+PREFILL_TRAFFIC_BYTES = None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--dense-iters", type=int, default=2)
+    ap.add_argument("--decode-caches", type=int, default=6)
+    ap.add_argument("--cpu-rows", type=int, default=512)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2503_03588_amd import binding as pa
+    from paper_2503_03588_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda"
+
+    # ---------------- workload ----------------
+    P = dict(batch=1, hq=32, hkv=8, n=131072, d=128, B=128, W=4, S=1, seed=2)          # configuration 3
+    Dc = dict(batch=16, hq=32, hkv=8, cap=65536, d=128, B=64, W=4, S=1, seed=3)         # configuration 4
+    pat_p = pa.Pattern(P["B"], P["W"], P["S"])
+    pat_d = pa.Pattern(Dc["B"], Dc["W"], Dc["S"])
+
+    q, k, v = synth.qkv(P["batch"], P["hq"], P["hkv"], P["n"], P["d"], "bf16", P["seed"])
+    qg, kg, vg = q.to(dev), k.to(dev), v.to(dev)
+    og = torch.empty_like(qg)
+    lseg = torch.empty((P["batch"], P["hq"], P["n"]), dtype=torch.float32, device=dev)
+    nb = pa.num_blocks(pat_p, P["n"])
+    mk = pa.max_k(pat_p, P["n"])
+    cnt = torch.empty((nb,), dtype=torch.int32, device=dev)
+    idx = torch.empty((nb, mk), dtype=torch.int32, device=dev)
+
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(Dc["seed"])
+    caches = []
+    for _ in range(args.decode_caches):
+        kc = torch.randn(Dc["batch"], Dc["hkv"], Dc["cap"], Dc["d"], device=dev, dtype=torch.bfloat16, generator=gen)
+        vc = torch.randn(Dc["batch"], Dc["hkv"], Dc["cap"], Dc["d"], device=dev, dtype=torch.bfloat16, generator=gen)
+        caches.append((kc, vc))
+    qd = torch.randn(Dc["batch"], Dc["hq"], Dc["d"], device=dev, dtype=torch.bfloat16, generator=gen)
+    lens = torch.full((Dc["batch"],), Dc["cap"], dtype=torch.int32, device=dev)
+    od = torch.empty_like(qd)
+    lsed = torch.empty((Dc["batch"], Dc["hq"]), dtype=torch.float32, device=dev)
+    ws = pa.decode_workspace(pat_d, Dc["batch"], Dc["hq"], Dc["hkv"], Dc["d"], Dc["cap"])
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def step(s, marks=None):
+        pa.mask_build(pat_p, P["n"], kv_cnt=cnt, kv_idx=idx)
+        if marks is not None:
+            marks[0].record()
+        pa.prefill(pat_p, cnt, idx, qg, kg, vg, o=og, lse=lseg)
+        if marks is not None:
+            marks[1].record()
+        kc, vc = caches[s % len(caches)]
+        pa.decode(pat_d, qd, kc, vc, lens, o=od, lse=lsed, workspace=ws)
+        if marks is not None:
+            marks[2].record()
+
+    for s in range(args.warmup):
+        step(s)
+    torch.cuda.synchronize()
+    marks = [(ev(), ev(), ev()) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(s, marks[s])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    prefill_ms = sum(m[0].elapsed_time(m[1]) for m in marks) / args.steps
+    decode_us = sum(m[1].elapsed_time(m[2]) for m in marks) / args.steps * 1e3
+
+    pairs = int(cnt.sum().item())
+    f_block = 4.0 * P["B"] * P["B"] * P["d"] * P["hq"] * P["batch"] * pairs      # attended blocks, diagonal whole
+    value = f_block / (ms_per_step * 1e-3) / 1e12
+    prefill_tflops = f_block / (prefill_ms * 1e-3) / 1e12
+
+    row = pa.row_host(pat_d, (Dc["cap"] - 1) // Dc["B"])
+    decode_bytes = len(row) * Dc["B"] * Dc["d"] * 2 * 2 * Dc["hkv"] * Dc["batch"]   # attended K and V tokens
+    decode_gbs = decode_bytes / (decode_us * 1e-6) / 1e9
+
+    # ---------------- dense causal baseline of the same library (outside the timed region) ----------------
+    dense = None
+    if not args.no_dense:
+        pat_dense = pa.Pattern(P["B"], P["W"], P["S"], flags=pa.DENSE)
+        o2 = torch.empty_like(qg)
+        pa.prefill(pat_dense, None, None, qg, kg, vg, o=o2, want_lse=False)
+        torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(args.dense_iters):
+            pa.prefill(pat_dense, None, None, qg, kg, vg, o=o2, want_lse=False)
+        e1.record()
+        torch.cuda.synchronize()
+        dense_ms = e0.elapsed_time(e1) / args.dense_iters
+        f_dense = 4.0 * P["d"] * P["hq"] * P["batch"] * (P["n"] * (P["n"] + 1) / 2)
+        dense = {"ms": round(dense_ms, 3), "tflops_causal": round(f_dense / (dense_ms * 1e-3) / 1e12, 1),
+                 "speedup_sparse_vs_dense": round(dense_ms / prefill_ms, 2),
+                 "block_pair_ratio": round((nb * (nb + 1) / 2) / pairs, 2)}
+        del o2
+
+    # ---------------- CPU oracle on a bounded row sample (also the bench's own parity check) ----------------
+    cpu = None
+    parity = None
+    if not args.no_cpu_baseline:
+        from oracle import powattn_oracle as orc
+        rng = np.random.default_rng(12345)
+        rows = sorted(set(rng.integers(0, P["n"], size=args.cpu_rows - 64).tolist())
+                      | set(range(P["n"] - 64, P["n"])))
+        rows_t = torch.tensor(rows, dtype=torch.long)
+        q_rows = synth.to_numpy_storage(q[:, :, rows_t])
+        ks, vs = synth.to_numpy_storage(k), synth.to_numpy_storage(v)
+        c0 = time.perf_counter()
+        oo, olse = orc.attention_rows(q_rows, ks, vs, rows, orc.Pattern(P["B"], P["W"], P["S"]),
+                                      q_holds_rows_only=True)
+        c1 = time.perf_counter()
+        cores = len(os.sched_getaffinity(0))
+        if os.environ.get("OMP_NUM_THREADS", "").isdigit():
+            cores = min(cores, int(os.environ["OMP_NUM_THREADS"]))
+        cpu_tflops = f_block * (len(rows) / P["n"]) / (c1 - c0) / 1e12
+        cpu = {"value": cpu_tflops, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+               "sample": f"{len(rows)} query rows (seeded random + the last 64) x all 32 heads of the 128K workload, "
+                         f"each against all 131072 keys in float64; {c1 - c0:.1f} s; FLOPs credited as for the GPU "
+                         f"(attended blocks only, scaled by rows/N)"}
+        go = og[:, :, rows_t.to(dev)].double().cpu().numpy()
+        gl = lseg[:, :, rows_t.to(dev)].double().cpu().numpy()
+        parity = {"prefill_rows_checked": len(rows) * P["hq"],
+                  "max_abs_err_o": float(np.abs(go - oo).max()), "max_abs_err_lse": float(np.abs(gl - olse).max())}
+
+    out = {
+        "metric": "sparse-attn prefill effective TFLOP/s (attended blocks only) at 128K",
+        "value": round(value, 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "step = mask_build + sparse prefill (b1, 32q/8kv heads, N=131072, D=128, block 128, "
+                               "W=4, S=1, bf16) + one decode step (b16, 32q/8kv, 65536-token bf16 caches, block 64, "
+                               "W=4, S=1, cold: rotating over %d caches)" % len(caches),
+                   "attended_block_pairs": pairs, "flops_per_step": f_block},
+        "roofline": {"bound": "mfma", "kernel": "pa_prefill_bf16_kernel", "achieved": round(prefill_tflops, 2),
+                     "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(prefill_tflops / PEAK_MFMA_BF16_TFLOPS, 4),
+                     "avg_launch_ms": round(prefill_ms, 4), "traffic": PREFILL_TRAFFIC_BYTES},
+        "cpu_baseline": cpu,
+        "decode": {"tokens_per_s": round(Dc["batch"] / (decode_us * 1e-6), 1), "us_per_step": round(decode_us, 2),
+                   "roofline": {"bound": "hbm", "kernel": "pa_decode_kernel (+ merge)", "achieved": round(decode_gbs, 1),
+                                "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(decode_gbs / PEAK_HBM_GBS, 4),
+                                "bytes_per_step": decode_bytes, "traffic": None}},
+        "dense_baseline": dense,
+        "parity": parity,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -131,7 +131,8 @@ int powattn_prefill(const powattn_pattern* pattern,
 
 /*
  * Bytes of device workspace powattn_decode needs for caches of up to
- * `cache_capacity` tokens (0 on invalid arguments).
+ * `cache_capacity` tokens (0 on invalid arguments).  It holds the split-K
+ * partial results when a (sequence, KV head) is spread over several workgroups.
  */
 size_t powattn_decode_workspace_bytes(const powattn_pattern* pattern, int32_t batch,
                                       int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
@@ -152,7 +153,8 @@ size_t powattn_decode_workspace_bytes(const powattn_pattern* pattern, int32_t ba
  *   lse            device float [batch, n_q_heads] or NULL
  *   dtype          POWATTN_BF16 only; head_dim 64 or 128; block a multiple of 64
  *   workspace      device, at least powattn_decode_workspace_bytes(...) bytes,
- *                  256-byte aligned; contents on entry are ignored
+ *                  256-byte aligned; contents on entry are ignored.  Two calls
+ *                  that may run at the same time must not share a workspace.
  * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR.
  */
 int powattn_decode(const powattn_pattern* pattern,

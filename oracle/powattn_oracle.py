@@ -197,14 +197,17 @@ def _softmax_rows(s, allowed, v):
     return o, lse
 
 
-def attention_rows(q, k, v, rows, pat: Pattern, scale=None):
+def attention_rows(q, k, v, rows, pat: Pattern, scale=None, q_holds_rows_only=False):
     """Equation 1 for the query positions `rows` only.
 
     q: [batch, Hq, N, D]; k, v: [batch, Hkv, N, D]; query head h reads KV head
     h // (Hq // Hkv).  Returns o[batch, Hq, len(rows), D], lse[batch, Hq, len(rows)].
+    With q_holds_rows_only, q is [batch, Hq, len(rows), D] and already holds just
+    the queries at positions `rows` (saves widening a long Q for a few rows).
     """
     q, k, v = widen(q), widen(k), widen(v)
-    batch, hq, n, d = q.shape
+    batch, hq, _, d = q.shape
+    n = k.shape[2]
     hkv = k.shape[1]
     g = hq // hkv
     if scale is None:
@@ -215,7 +218,8 @@ def attention_rows(q, k, v, rows, pat: Pattern, scale=None):
     lse = np.empty((batch, hq, rows.size), dtype=np.float64)
     for b in range(batch):
         for h in range(hq):
-            s = scale * (q[b, h, rows] @ k[b, h // g].T)
+            qr = q[b, h] if q_holds_rows_only else q[b, h, rows]
+            s = scale * (qr @ k[b, h // g].T)
             o[b, h], lse[b, h] = _softmax_rows(s, allowed, v[b, h // g])
     return o, lse
 

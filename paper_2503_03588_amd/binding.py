@@ -158,6 +158,14 @@ def decode_workspace_bytes(pattern: Pattern, batch, n_q_heads, n_kv_heads, head_
                                                 head_dim, cache_capacity)
 
 
+def decode_workspace(pattern: Pattern, batch, n_q_heads, n_kv_heads, head_dim, cache_capacity, device="cuda"):
+    """An uninitialised workspace of the size powattn_decode asks for."""
+    need = decode_workspace_bytes(pattern, batch, n_q_heads, n_kv_heads, head_dim, cache_capacity)
+    if need == 0:
+        raise PowattnError(INVALID_ARG, "powattn_decode_workspace_bytes")
+    return torch.empty((need,), dtype=torch.uint8, device=device)
+
+
 # ---- device entry points ---------------------------------------------------------
 def mask_build(pattern: Pattern, seq_len: int, kv_cnt=None, kv_idx=None, block_mask=None,
                want_block_mask=False, device="cuda", stream=None):
@@ -215,7 +223,7 @@ def decode(pattern: Pattern, q, k_cache, v_cache, kv_len, o=None, lse=None, soft
         lse = torch.empty((batch, hq), dtype=torch.float32, device=q.device)
     if workspace is None:
         need = decode_workspace_bytes(pattern, batch, hq, hkv, d, cap)
-        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=q.device)
+        workspace = decode_workspace(pattern, batch, hq, hkv, d, cap, q.device)
     st = lib().powattn_decode(ctypes.byref(pattern.c()), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(kv_len),
                               cap, _ptr(o), _ptr(lse), batch, hq, hkv, d, _dtype_code(q),
                               float(softmax_scale), _ptr(workspace), workspace.numel() * workspace.element_size(),

@@ -59,12 +59,9 @@ extern "C" int32_t powattn_max_k(const powattn_pattern* p, int64_t seq_len) {
   int64_t nb = powattn_num_blocks(p, seq_len);
   if (nb < 0) return (int32_t)nb;
   if (p->flags & POWATTN_DENSE) return (int32_t)nb;
-  int64_t best = 0;
-  for (int64_t i = 0; i < nb; ++i) {
-    int64_t n = pa_for_each_block(p->window, p->sink, p->flags, i, [](int64_t) {});
-    if (n > best) best = n;
-  }
-  return (int32_t)best;
+  // Rows up to W+S-1 attend every earlier block (i+1 of them); beyond that the count is
+  // W + S + #{k : W <= 2^k <= i-S}, which only grows with i.  The last row is the longest.
+  return (int32_t)pa_for_each_block(p->window, p->sink, p->flags, nb - 1, [](int64_t) {});
 }
 
 static bool supported_head_dim(int32_t d) { return d == 64 || d == 128; }
@@ -112,9 +109,10 @@ extern "C" size_t powattn_decode_workspace_bytes(const powattn_pattern* pattern,
   if (pa_check_pattern(pattern) != POWATTN_OK) return 0;
   if (batch < 1 || n_q_heads < 1 || n_kv_heads < 1 || head_dim < 1 || cache_capacity < 1) return 0;
   if (n_q_heads % n_kv_heads != 0) return 0;
-  int32_t ns = pa_decode_splits(pattern, cache_capacity);
+  int32_t ns = pa_decode_splits(pattern, batch, n_kv_heads, cache_capacity);
   if (ns < 1) return 0;
-  // per (batch, q head, split): head_dim partial outputs + running max + running sum
+  // per (batch, q head, split): head_dim unnormalised outputs + running max + running sum.
+  // With a single split the kernel writes the result directly and the buffer is not touched.
   size_t partials = (size_t)batch * n_q_heads * ns * (size_t)(head_dim + 2) * sizeof(float);
   return (partials + 255) & ~(size_t)255;
 }
@@ -150,7 +148,7 @@ extern "C" int powattn_decode(const powattn_pattern* pattern,
   a.batch = batch; a.hq = n_q_heads; a.hkv = n_kv_heads; a.head_dim = head_dim;
   a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)head_dim);
   a.workspace = workspace;
-  a.n_split = pa_decode_splits(pattern, cache_capacity);
+  a.n_split = pa_decode_splits(pattern, batch, n_kv_heads, cache_capacity);
   a.stream = (hipStream_t)hip_stream;
   return pa_launch_decode_bf16(a);
 }

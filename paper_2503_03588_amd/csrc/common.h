@@ -37,8 +37,8 @@ struct pa_decode_args {
   int32_t batch, hq, hkv, head_dim;
   float scale;
   void* workspace;
-  int32_t n_split;   // partial slots per (batch, kv head)
+  int32_t n_split;   // workgroups per (batch, kv head)
   hipStream_t stream;
 };
 int pa_launch_decode_bf16(const pa_decode_args& a);
-int32_t pa_decode_splits(const powattn_pattern* pat, int64_t capacity);
+int32_t pa_decode_splits(const powattn_pattern* pat, int32_t batch, int32_t hkv, int64_t capacity);

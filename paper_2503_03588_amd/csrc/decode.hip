@@ -1,3 +1,331 @@
+// Split-K decode: one query token per sequence attends its KV cache under the
+// prefill pattern (Section 4.1: the same pattern in both phases).  The query
+// sits at t = kv_len-1; the attended block list of row floor(t/B) comes from
+// the closed form of Algorithm 1, inside the kernel.
+//
+// The step reads 2*D*2 bytes per attended token and does a handful of flops
+// with them: it is bound by HBM bandwidth and latency, so the kernel is built
+// around having every byte in flight at once and keeping the dependent chain
+// after the loads short.
+//
+//  * A workgroup of 8 wavefronts owns one (sequence, KV head[, split]).  The
+//    attended tokens are cut into 64-token chunks; wavefront w takes chunks
+//    w, w+8, ... and issues all K and V loads of a chunk before touching any.
+//  * Everything stays in registers.  K rows are loaded straight into the
+//    A-operand layout of v_mfma_f32_16x16x32_bf16 (S^T = K q^T, the G query
+//    heads of the group are the 16 columns, unused ones zero).  V is loaded
+//    fully coalesced as 8 tokens x 8 d per lane and transposed inside the lane
+//    (32 byte-permutes per 8x8 block) into the A operand of O^T += V^T P^T.
+//    The K rows are fetched in a permuted token order chosen so that the
+//    accumulator layout of S^T is the B-operand layout of the second product.
+//  * Each wavefront keeps a running (max, sum, O) over its chunks; the eight
+//    partials meet in LDS.  With one workgroup per (sequence, KV head) that is
+//    the result; with several (small batches) the workgroups leave
+//    unnormalised partials in the workspace and a second, tiny kernel merges.
+#include <math.h>
 #include "common.h"
-int32_t pa_decode_splits(const powattn_pattern* pat, int64_t capacity) { (void)pat; (void)capacity; return 1; }
-int pa_launch_decode_bf16(const pa_decode_args& a) { (void)a; return POWATTN_UNSUPPORTED; }
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int CH = 64;         // tokens per chunk
+constexpr int NW = 8;          // wavefronts per workgroup
+constexpr int MAXG = 16;       // query heads per KV head (columns of the MFMA tile)
+
+struct dec_params {
+  const __bf16* q; const __bf16* k; const __bf16* v; const int32_t* kv_len;
+  __bf16* o; float* lse;
+  float* partials;      // [batch, hq, splits, D + 2] when splits > 1
+  int64_t capacity;
+  int32_t B, W, S; uint32_t flags;
+  int32_t hq, hkv, G, splits, subs;
+  float c2;
+};
+
+template <int D>
+__global__ __launch_bounds__(64 * NW) void pa_decode_kernel(dec_params p) {
+  constexpr int NC = D / 32;     // 32-wide steps of the head dimension in S^T = K q^T
+  constexpr int CPR = D / 8;     // 16-byte pieces per row; lane%16 >= CPR idles in the V path (D = 64)
+  __shared__ float s_m[NW][MAXG], s_l[NW][MAXG];
+  extern __shared__ float s_o_dyn[];            // [NW][G][D] partial outputs of the wavefronts
+
+  const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int g = lane & 15, q4 = lane >> 4;    // column (query head) and k-group of this lane
+
+  int64_t len = p.kv_len[b];
+  if (len < 1) len = 1;
+  if (len > p.capacity) len = p.capacity;
+  const int64_t t = len - 1;
+  const int64_t i = t / p.B;
+
+  // q^T fragments: column g, 8 consecutive d per 32-wide step
+  bf16x8 qf[NC];
+  {
+    const bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+    const __bf16* qp = p.q + ((int64_t)b * p.hq + (int64_t)kvh * p.G + (g < p.G ? g : 0)) * D;
+#pragma unroll
+    for (int c = 0; c < NC; ++c)
+      qf[c] = g < p.G ? *reinterpret_cast<const bf16x8*>(qp + 32 * c + 8 * q4) : z;
+  }
+  // Row i in closed form: [0, sink_end) ++ {i - 2^k inside [pow_lo, win_start), k descending} ++ [win_start, i].
+  // All of this is uniform over the workgroup, so it runs on the scalar unit of every wavefront.
+  const pa_row_shape rs = pa_shape_of_row(p.W, p.S, p.flags, i);
+  int n_pow = 0;
+  int64_t p_top = 1;                       // largest power of two <= i
+  while ((p_top << 1) <= i) p_top <<= 1;
+  if (p.flags & POWATTN_POWER)
+    for (int64_t pw = p_top; pw >= 1; pw >>= 1) {
+      const int64_t jj = i - pw;
+      n_pow += (jj >= rs.pow_lo && jj < rs.win_start) ? 1 : 0;
+    }
+  const int n_blocks = (int)rs.sink_end + n_pow + (int)(i - rs.win_start + 1);
+  const int n_slots = n_blocks * p.subs;
+  auto block_at = [&](int lp) -> int64_t {   // lp-th attended block of the row
+    if (lp < rs.sink_end) return lp;
+    lp -= (int)rs.sink_end;
+    if (lp >= n_pow) return rs.win_start + (lp - n_pow);
+    int seen = 0;
+    for (int64_t pw = p_top; pw >= 1; pw >>= 1) {
+      const int64_t jj = i - pw;
+      if (jj >= rs.pow_lo && jj < rs.win_start) { if (seen == lp) return jj; ++seen; }
+    }
+    return i;                                // not reached
+  };
+
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x4 O[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) O[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const __bf16* kslab = p.k + ((int64_t)b * p.hkv + kvh) * p.capacity * D;
+  const __bf16* vslab = p.v + ((int64_t)b * p.hkv + kvh) * p.capacity * D;
+
+  for (int slot = split * NW + wave; slot < n_slots; slot += p.splits * NW) {
+    const int64_t tok0 = block_at(slot / p.subs) * p.B + (int64_t)(slot % p.subs) * CH;
+    const int64_t left = t + 1 - tok0;                 // causal: tokens tok0..t are attended
+    if (left <= 0) continue;                           // chunk of the diagonal block beyond the query
+    const int n_tok = left >= CH ? CH : (int)left;
+    const __bf16* kb = kslab + tok0 * D;
+    const __bf16* vb = vslab + tok0 * D;
+
+    // ---- issue every load of the chunk ----
+    // K tile 2x+y, row rho = lane%16 holds token 32x + 8(rho/4) + 4y + rho%4: with this order the S^T
+    // accumulator of lane (g, q4) holds tokens 32x + 8*q4 + (0..7), which is what P^T must supply below.
+    u32x4 kraw[4][NC];
+#pragma unroll
+    for (int tau = 0; tau < 4; ++tau) {
+      const int tk = 32 * (tau >> 1) + 8 * (g >> 2) + 4 * (tau & 1) + (g & 3);
+#pragma unroll
+      for (int c = 0; c < NC; ++c)
+        kraw[tau][c] = tk < n_tok ? *reinterpret_cast<const u32x4*>(kb + tk * D + 32 * c + 8 * q4) : u32x4{0, 0, 0, 0};
+    }
+    // V: lane (dg = lane%16, tg = lane/16) takes tokens 32x + 8tg + (0..7), d = 8dg .. 8dg+7
+    u32x4 vraw[2][8];
+#pragma unroll
+    for (int x = 0; x < 2; ++x)
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        const int tk = 32 * x + 8 * q4 + r;
+        vraw[x][r] = (g < CPR && tk < n_tok) ? *reinterpret_cast<const u32x4*>(vb + tk * D + 8 * g) : u32x4{0, 0, 0, 0};
+      }
+
+    // ---- S^T = K q^T ----
+    f32x4 S[4];
+#pragma unroll
+    for (int tau = 0; tau < 4; ++tau) {
+      S[tau] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int c = 0; c < NC; ++c)
+        S[tau] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kraw[tau][c]), qf[c], S[tau], 0, 0, 0);
+    }
+
+    // ---- online softmax; S[2x+y][r] is token 32x + 8*q4 + 4y + r of head g ----
+    float mx = -INFINITY;
+#pragma unroll
+    for (int tau = 0; tau < 4; ++tau)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int tk = 32 * (tau >> 1) + 8 * q4 + 4 * (tau & 1) + r;
+        S[tau][r] = tk < n_tok ? S[tau][r] * p.c2 : -INFINITY;
+        mx = fmaxf(mx, S[tau][r]);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 16));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));                // finite: token 0 of the chunk is attended
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    m_run = m_new;
+    float rowsum = 0.f;
+#pragma unroll
+    for (int tau = 0; tau < 4; ++tau)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        S[tau][r] = __builtin_amdgcn_exp2f(S[tau][r] - m_new);
+        rowsum += S[tau][r];
+      }
+    l_run = l_run * alpha + rowsum;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) O[j][r] *= alpha;
+
+    // ---- O^T += V^T P^T: 32 tokens per step; MFMA j covers d = 8*row + j ----
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+      bf16x8 pf;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) pf[e] = (__bf16)S[2 * x + (e >> 2)][e & 3];
+      // transpose the lane's 8 tokens x 8 d block: pairs of tokens share a dword
+      uint32_t tr[4][8];                                // tr[a][d]: tokens 2a, 2a+1 at d
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int kd = 0; kd < 4; ++kd) {
+          const uint32_t r0 = vraw[x][2 * a][kd], r1 = vraw[x][2 * a + 1][kd];
+          tr[a][2 * kd] = __builtin_amdgcn_perm(r1, r0, 0x05040100u);       // low halves: d = 2kd
+          tr[a][2 * kd + 1] = __builtin_amdgcn_perm(r1, r0, 0x07060302u);   // high halves: d = 2kd+1
+        }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const u32x4 vf = {tr[0][j], tr[1][j], tr[2][j], tr[3][j]};
+        O[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf), pf, O[j], 0, 0, 0);
+      }
+    }
+  }
+
+  // ---- merge the wavefronts: lane (g, q4) holds O[j][r] = o[g][d = 8(4*q4 + r) + j] ----
+  l_run += __shfl_xor(l_run, 16);
+  l_run += __shfl_xor(l_run, 32);
+  if (g < p.G) {
+    if (q4 == 0) { s_m[wave][g] = m_run; s_l[wave][g] = l_run; }
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int d = 8 * (4 * q4 + r) + j;
+        if (d < D) s_o_dyn[((wave * p.G) + g) * D + d] = O[j][r];
+      }
+  }
+  __syncthreads();
+
+  for (int e = tid; e < p.G * D; e += 64 * NW) {
+    const int gg = e / D, d = e % D;
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) M = fmaxf(M, s_m[w][gg]);
+    float L = 0.f, acc = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const float wt = s_l[w][gg] > 0.f ? __builtin_amdgcn_exp2f(s_m[w][gg] - M) : 0.f;
+      L = fmaf(wt, s_l[w][gg], L);
+      acc = fmaf(wt, s_o_dyn[((w * p.G) + gg) * D + d], acc);
+    }
+    const int h = kvh * p.G + gg;
+    if (p.splits == 1) {
+      p.o[((int64_t)b * p.hq + h) * D + d] = (__bf16)(acc / L);      // L > 0: chunk 0 of the row is never empty
+      if (p.lse && d == 0) p.lse[(int64_t)b * p.hq + h] = (M + log2f(L)) * 0.69314718055994530942f;
+    } else {
+      float* part = p.partials + (((int64_t)b * p.hq + h) * p.splits + split) * (D + 2);
+      part[d] = acc;
+      if (d == 0) { part[D] = M; part[D + 1] = L; }                  // an idle split leaves M = -inf, L = 0
+    }
+  }
+}
+
+// Merges the partials of the splits: one wavefront per (sequence, query head).  The loads of
+// eight splits are issued together so that their latencies overlap.
+template <int D>
+__global__ __launch_bounds__(64) void pa_decode_merge_kernel(dec_params p) {
+  constexpr int DPL = D / 64;
+  const int h = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
+  const float* part = p.partials + ((int64_t)b * p.hq + h) * p.splits * (D + 2);
+  float M = -INFINITY, L = 0.f;
+  float acc[DPL];
+#pragma unroll
+  for (int e = 0; e < DPL; ++e) acc[e] = 0.f;
+  for (int s0 = 0; s0 < p.splits; s0 += 8) {
+    float m8[8], l8[8], o8[8][DPL];
+#pragma unroll
+    for (int x = 0; x < 8; ++x) {
+      const int s = s0 + x < p.splits ? s0 + x : p.splits - 1;    // clamp: stay inside the row of partials
+      const float* ps = part + (int64_t)s * (D + 2);
+      m8[x] = ps[D];
+      l8[x] = s0 + x < p.splits ? ps[D + 1] : 0.f;
+#pragma unroll
+      for (int e = 0; e < DPL; ++e) o8[x][e] = ps[lane + 64 * e];
+    }
+    float Mn = M;
+#pragma unroll
+    for (int x = 0; x < 8; ++x) if (l8[x] > 0.f) Mn = fmaxf(Mn, m8[x]);
+    const float resc = L > 0.f ? __builtin_amdgcn_exp2f(M - Mn) : 0.f;
+    L *= resc;
+#pragma unroll
+    for (int e = 0; e < DPL; ++e) acc[e] *= resc;
+#pragma unroll
+    for (int x = 0; x < 8; ++x) {
+      if (l8[x] > 0.f) {                                          // idle splits wrote no outputs
+        const float wt = __builtin_amdgcn_exp2f(m8[x] - Mn);
+        L = fmaf(wt, l8[x], L);
+#pragma unroll
+        for (int e = 0; e < DPL; ++e) acc[e] = fmaf(wt, o8[x][e], acc[e]);
+      }
+    }
+    M = Mn;
+  }
+#pragma unroll
+  for (int e = 0; e < DPL; ++e) p.o[((int64_t)b * p.hq + h) * D + lane + 64 * e] = (__bf16)(acc[e] / L);
+  if (p.lse && lane == 0) p.lse[(int64_t)b * p.hq + h] = (M + log2f(L)) * 0.69314718055994530942f;
+}
+
+}  // namespace
+
+// Workgroups per (sequence, KV head).  A workgroup has all loads of eight 64-token chunks in
+// flight at once; a second pass over further chunks would pay the memory latency again, so a row
+// with more chunks is cut into several workgroups whose partials a small second kernel merges.
+// Small batches are cut further so that more of the 256 compute units pull on the memory system.
+int32_t pa_decode_splits(const powattn_pattern* pat, int32_t batch, int32_t hkv, int64_t capacity) {
+  const int32_t mk = powattn_max_k(pat, capacity);
+  if (mk < 1) return 0;
+  const int64_t slots = (int64_t)mk * (pat->block / CH);
+  const int64_t base = (int64_t)batch * hkv;
+  int64_t s = (slots + NW - 1) / NW;                 // one pass per workgroup
+  if (s > 8) s = 8;
+  if (base * s < 256) {                              // not enough workgroups to cover the chip
+    int64_t want = (256 + base - 1) / base;
+    const int64_t cap = slots / 2 > 1 ? slots / 2 : 1;
+    if (want > cap) want = cap;
+    if (want > s) s = want;
+  }
+  if (s > 1024) s = 1024;
+  return (int32_t)s;
+}
+
+int pa_launch_decode_bf16(const pa_decode_args& a) {
+  if (a.n_split < 1) return POWATTN_UNSUPPORTED;
+  if (a.hkv > 65535 || a.batch > 65535 || a.hq > 65535 * 16) return POWATTN_UNSUPPORTED;
+  dec_params p;
+  p.q = (const __bf16*)a.q; p.k = (const __bf16*)a.k; p.v = (const __bf16*)a.v; p.kv_len = a.kv_len;
+  p.o = (__bf16*)a.o; p.lse = a.lse;
+  p.partials = (float*)a.workspace;
+  p.capacity = a.capacity;
+  p.B = a.pat.block; p.W = a.pat.window; p.S = a.pat.sink; p.flags = a.pat.flags;
+  p.hq = a.hq; p.hkv = a.hkv; p.G = a.hq / a.hkv; p.splits = a.n_split; p.subs = a.pat.block / CH;
+  p.c2 = a.scale * 1.44269504088896340736f;
+  dim3 grid((uint32_t)a.n_split, (uint32_t)a.hkv, (uint32_t)a.batch);
+  const size_t lds = (size_t)NW * p.G * a.head_dim * sizeof(float);   // at most 64 KB (G <= 16, D <= 128)
+  if (a.head_dim == 128)
+    hipLaunchKernelGGL((pa_decode_kernel<128>), grid, dim3(64 * NW), lds, a.stream, p);
+  else
+    hipLaunchKernelGGL((pa_decode_kernel<64>), grid, dim3(64 * NW), lds, a.stream, p);
+  int st = pa_note_hip(hipGetLastError());
+  if (st != POWATTN_OK || a.n_split == 1) return st;
+  dim3 mgrid((uint32_t)a.hq, (uint32_t)a.batch);
+  if (a.head_dim == 128)
+    hipLaunchKernelGGL((pa_decode_merge_kernel<128>), mgrid, dim3(64), 0, a.stream, p);
+  else
+    hipLaunchKernelGGL((pa_decode_merge_kernel<64>), mgrid, dim3(64), 0, a.stream, p);
+  return pa_note_hip(hipGetLastError());
+}

@@ -1,0 +1,99 @@
+"""GPU parity: powattn_decode (split-K over the attended blocks) vs the oracle.
+Bar: max abs error 2e-2 on the outputs (bf16), 1e-3 on the log-sum-exp."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import powattn_oracle as orc
+from paper_2503_03588_amd import binding as pa
+from paper_2503_03588_amd import synth
+from gpu_util import TOL_LSE, TOL_O, oracle_pattern
+
+pytestmark = pytest.mark.gpu
+
+
+def run_decode(pat, batch, hq, hkv, cap, d, kv_len, seed, scale=0.0, calls=1):
+    q, k, v = synth.decode_inputs(batch, hq, hkv, cap, d, "bf16", seed)
+    lens = torch.tensor(kv_len, dtype=torch.int32)
+    ws = pa.decode_workspace(pat, batch, hq, hkv, d, cap)
+    ws.fill_(0xFF)                  # the library must not rely on the workspace's contents (0xFF.. = NaN)
+    qd, kd, vd, ld = q.cuda(), k.cuda(), v.cuda(), lens.cuda()
+    for c in range(calls):          # the workspace is reused: counters must come back to zero, and
+        if c < calls - 1:           # partials of an earlier call with other data must not leak into this one
+            pa.decode(pat, -qd, vd, kd, ld, softmax_scale=scale, workspace=ws)
+        o, lse = pa.decode(pat, qd, kd, vd, ld, softmax_scale=scale, workspace=ws)
+    torch.cuda.synchronize()
+    go, glse = o.double().cpu().numpy(), lse.double().cpu().numpy()
+    assert np.isfinite(go).all() and np.isfinite(glse).all()
+    oo, olse = orc.decode(synth.to_numpy_storage(q), synth.to_numpy_storage(k), synth.to_numpy_storage(v),
+                          np.asarray(kv_len), oracle_pattern(pat), None if scale <= 0 else scale)
+    err_o, err_l = np.abs(go - oo).max(), np.abs(glse - olse).max()
+    assert err_o <= TOL_O["bf16"], err_o
+    assert err_l <= TOL_LSE, err_l
+    return qd, kd, vd, ld, go, glse
+
+
+@pytest.mark.parametrize("B,W,S,hq,hkv,d,cap,kv_len", [
+    (64, 4, 1, 8, 2, 128, 4096, [4096, 4095, 1, 64, 65, 2049, 3000, 100]),
+    (64, 4, 0, 4, 1, 128, 2048, [2048, 1025]),
+    (128, 4, 1, 8, 2, 128, 4096, [4096, 129, 128, 127]),          # two 64-token chunks per block
+    (256, 5, 1, 4, 2, 64, 8192, [8192, 5000, 300]),               # paper's block size; head_dim 64
+    (64, 2, 1, 7, 1, 128, 3000, [3000, 2999, 777]),               # GQA 7: two heads per wavefront; ragged capacity
+    (64, 4, 1, 16, 1, 128, 1024, [1000]),                         # GQA 16
+    (64, 3, 1, 2, 2, 128, 2048, [2048, 1]),                       # no GQA
+    (64, 0, 0, 4, 2, 128, 4096, [4096, 4033]),                    # W = 0
+])
+def test_shapes_and_lengths(B, W, S, hq, hkv, d, cap, kv_len):
+    run_decode(pa.Pattern(B, W, S), len(kv_len), hq, hkv, cap, d, kv_len, seed=31, calls=2)
+
+
+def test_sliding_window_flag_and_scale():
+    run_decode(pa.Pattern(64, 5, 1, flags=0), 2, 4, 2, 2048, 128, [2048, 900], seed=32, scale=0.11)
+
+
+def test_config4_shape_reduced_batch():
+    # config 4 (batch 16, 32/8 heads, 65536-token cache) at batch 2 so the oracle and the upload stay small
+    run_decode(pa.Pattern(64, 4, 1), 2, 32, 8, 65536, 128, [65536, 65535], seed=3)
+
+
+def test_decode_equals_prefill_row():
+    pat = pa.Pattern(64, 4, 1)
+    n, hq, hkv, d = 2048, 8, 2, 128
+    q, k, v = synth.qkv(1, hq, hkv, n, d, "bf16", seed=33)
+    cnt, idx, _ = pa.mask_build(pat, n)
+    o, lse = pa.prefill(pat, cnt, idx, q.cuda(), k.cuda(), v.cuda())
+    for t in (2047, 1984, 1000, 63, 0):
+        od, ld = pa.decode(pat, q[:, :, t].contiguous().cuda(), k.cuda(), v.cuda(),
+                           torch.tensor([t + 1], dtype=torch.int32).cuda())
+        torch.cuda.synchronize()
+        assert (od.float() - o[:, :, t].float()).abs().max().item() <= 2e-2
+        assert (ld - lse[:, :, t]).abs().max().item() <= 1e-3
+
+
+def test_out_of_range_lengths_are_clamped():
+    pat = pa.Pattern(64, 4, 1)
+    qd, kd, vd, _, go, glse = run_decode(pat, 2, 4, 2, 1024, 128, [1024, 1], seed=34)
+    bad = torch.tensor([5000, -3], dtype=torch.int32).cuda()      # clamped to [1, capacity]
+    o, lse = pa.decode(pat, qd, kd, vd, bad)
+    torch.cuda.synchronize()
+    assert np.array_equal(o.double().cpu().numpy(), go)
+
+
+def test_full_size_config4():
+    # batch 16, 32 q / 8 kv heads, 65536-token caches; random draws happen on the GPU to keep the upload
+    # small, and the oracle sees the same bits copied back (only the attended blocks matter).
+    pat = pa.Pattern(64, 4, 1)
+    batch, hq, hkv, cap, d = 16, 32, 8, 65536, 128
+    g = torch.Generator(device="cuda"); g.manual_seed(3)
+    k = torch.randn(batch, hkv, cap, d, device="cuda", dtype=torch.bfloat16, generator=g)
+    v = torch.randn(batch, hkv, cap, d, device="cuda", dtype=torch.bfloat16, generator=g)
+    q = torch.randn(batch, hq, d, device="cuda", dtype=torch.bfloat16, generator=g)
+    lens = torch.full((batch,), cap, dtype=torch.int32, device="cuda")
+    lens[1] = cap - 37
+    o, lse = pa.decode(pat, q, k, v, lens)
+    torch.cuda.synchronize()
+    for b in (0, 1, 15):
+        oo, ol = orc.decode(synth.to_numpy_storage(q[b:b + 1]), synth.to_numpy_storage(k[b:b + 1]),
+                            synth.to_numpy_storage(v[b:b + 1]), [int(lens[b])], orc.Pattern(64, 4, 1))
+        assert np.abs(o[b:b + 1].double().cpu().numpy() - oo).max() <= 2e-2
+        assert np.abs(lse[b:b + 1].double().cpu().numpy() - ol).max() <= 1e-3

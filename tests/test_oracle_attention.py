@@ -109,6 +109,8 @@ def test_rows_subset_equals_full():
     rows = [0, 7, 8, 55, 99]
     o2, lse2 = orc.attention_rows(q, k, v, rows, pat)
     assert np.array_equal(o[:, :, rows], o2) and np.array_equal(lse[:, :, rows], lse2)
+    o3, lse3 = orc.attention_rows(q[:, :, rows], k, v, rows, pat, q_holds_rows_only=True)
+    assert np.array_equal(o2, o3) and np.array_equal(lse2, lse3)
 
 
 def test_decode_equals_prefill_row():
