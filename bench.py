@@ -41,6 +41,9 @@ def main():
     ap.add_argument("--dense-iters", type=int, default=2)
     ap.add_argument("--decode-caches", type=int, default=6)
     ap.add_argument("--cpu-rows", type=int, default=512)
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one elementwise copy of 1 GiB (reads 1 GiB, writes 1 GiB): the reference "
+                         "dispatch for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -98,6 +101,13 @@ def main():
         pa.decode(pat_d, qd, kc, vc, lens, o=od, lse=lsed, workspace=ws)
         if marks is not None:
             marks[2].record()
+
+    if args.calib_copy:
+        src = torch.ones((1 << 28,), dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     for s in range(args.warmup):
         step(s)

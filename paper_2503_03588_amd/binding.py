@@ -14,7 +14,7 @@ from dataclasses import dataclass
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libpowattn.so")
+LIB_PATH = os.environ.get("POWATTN_LIB") or os.path.join(_HERE, "libpowattn.so")
 
 OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR = 0, 1, 2, 3, 4
 POWER, DENSE = 1, 2

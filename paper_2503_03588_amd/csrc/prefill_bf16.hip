@@ -18,6 +18,16 @@
 // S^T is already the B-operand layout of the second product (the key order
 // inside a 16-key step is permuted identically for P^T and V^T, which a
 // contraction does not care about).
+//
+// Memory pipeline.  A query block attends only a dozen key blocks, so a tile's
+// compute (about a microsecond) is shorter than a trip to HBM: one tile of
+// prefetch leaves the matrix cores waiting.  K/V tiles therefore travel
+// global -> LDS asynchronously (global_load_lds_dwordx4, no registers in
+// between) into a ring of NS stages, NS-1 tiles ahead of the compute; a
+// wavefront waits on its own loads with s_waitcnt vmcnt(n) and one barrier per
+// tile makes the stage visible and frees the oldest one.  The asynchronous
+// copy cannot pad rows, so bank conflicts are avoided by a XOR swizzle of the
+// 16-byte chunk index with the row index, applied on the global-address side.
 #include <math.h>
 #include <stdlib.h>
 #include "common.h"
@@ -30,8 +40,10 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((address_space(3))) char lds_char;
 
-constexpr int KT = 64;  // keys per staged tile
+constexpr int KT = 64;          // keys per staged tile
+constexpr float RESCALE_TAU = 8.0f;   // running max is only raised when exceeded by 2^8 (see softmax below)
 
 struct bf16_params {
   const __bf16* q; const __bf16* k; const __bf16* v; __bf16* o; float* lse;
@@ -54,45 +66,92 @@ struct tile_pos {
   bool valid;
 };
 
-__device__ __forceinline__ int list_len(const bf16_params& p, int i) {
-  if (p.dense) return i + 1;
-  int n = p.kv_cnt[i];
-  return n < p.max_k ? n : p.max_k;
+// The block list of one query block is copied into LDS once; a lookup is then an LDS read made
+// wavefront-uniform with v_readfirstlane.  Going through LDS matters: a lookup from global memory
+// inside the tile loop would be a vector load, and waiting for it would also wait for every
+// asynchronous tile copy in flight.
+constexpr int LIST_CAP = 1024;   // longest block list the kernel accepts (the dense list is implicit)
+
+struct list_view {
+  const int* lds;   // the row in LDS
+  int n;            // entries
+  bool dense;
+};
+
+__device__ __forceinline__ int list_at(const list_view& L, int t) {
+  return L.dense ? t : __builtin_amdgcn_readfirstlane(L.lds[t]);
 }
 
 // first list position >= t whose entry is a causal block, or n
-__device__ __forceinline__ tile_pos seek(const bf16_params& p, int i, int n, int t) {
+__device__ __forceinline__ tile_pos seek(const list_view& L, int i, int t) {
   tile_pos r;
   r.u = 0;
-  for (; t < n; ++t) {
-    int j = p.dense ? t : p.kv_idx[(int64_t)i * p.max_k + t];
+  for (; t < L.n; ++t) {
+    const int j = list_at(L, t);
     if (j >= 0 && j <= i) { r.t = t; r.j = j; r.valid = true; return r; }
   }
-  r.t = n; r.j = 0; r.valid = false;
+  r.t = L.n; r.j = 0; r.valid = false;
   return r;
 }
 
-__device__ __forceinline__ tile_pos advance(const bf16_params& p, int i, int n, tile_pos c, int subs_diag) {
-  const int lim = (c.j == i) ? subs_diag : p.subs;
-  if (c.u + 1 < lim) { c.u += 1; return c; }
-  return seek(p, i, n, c.t + 1);
+// Positions are the same in every lane; saying so keeps the loop control on the scalar unit.
+__device__ __forceinline__ tile_pos uniform(tile_pos r) {
+  r.t = __builtin_amdgcn_readfirstlane(r.t);
+  r.j = __builtin_amdgcn_readfirstlane(r.j);
+  r.u = __builtin_amdgcn_readfirstlane(r.u);
+  r.valid = __builtin_amdgcn_readfirstlane((int)r.valid) != 0;
+  return r;
 }
 
-template <int D, int CT, int NW>
-__global__ __launch_bounds__(64 * NW) void pa_prefill_bf16_kernel(bf16_params p) {
+__device__ __forceinline__ tile_pos advance(const list_view& L, int i, tile_pos c, int subs, int subs_diag) {
+  const int lim = (c.j == i) ? subs_diag : subs;
+  if (c.u + 1 < lim) { c.u += 1; return uniform(c); }
+  return uniform(seek(L, i, c.t + 1));
+}
+
+// Asynchronous 16-byte-per-lane copy global -> LDS: lane l's data lands at lds_off + 16*l.
+// Written as inline assembly on purpose: the compiler then does not pair every later LDS read
+// with a full vmcnt(0) wait, and the waits are placed by hand (wait_vmcnt below).  M0 carries
+// the LDS offset; nothing else in this kernel uses M0.
+__device__ __forceinline__ void async_copy16(const void* gptr, uint32_t lds_off) {
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_off) : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {   // s_waitcnt vmcnt(N) only
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
+// XOR swizzle of the 16-byte chunk index inside a row, as a function of the row's low bits.
+// D = 128 (16 chunks per row): any 16 consecutive rows map one chunk column onto 16 different
+// bank groups (K fragment reads), and 4 consecutive rows x 4 consecutive chunks map onto 16
+// different bank groups (transposing V reads).  D = 64 (8 chunks per row, two rows per 256 B).
+template <int D>
+__device__ __forceinline__ int swz(int row) {
+  if (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
+  return (row >> 1) & 7;
+}
+
+template <int D, int CT, int NW, int NS>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(CT == 1 ? 2 : 1, CT == 1 ? 2 : 1)))
+void pa_prefill_bf16_kernel(bf16_params p) {
   constexpr int QW = 32 * CT;        // query tokens per wavefront
-  constexpr int NT = 64 * NW;
-  constexpr int KSTR = D + 8;        // LDS row pitch of K in elements: 16-lane groups of a b128 read hit distinct banks
-  constexpr int VSTR = D + 32;       // LDS row pitch of V: the 4 rows x 64 B of a transposing read hit distinct banks
-  constexpr int CPR = D / 8;         // 16-byte chunks per K/V row
-  constexpr int CHUNKS = KT * CPR;   // chunks per tile
-  constexpr int CPT = (CHUNKS + NT - 1) / NT;  // chunks per thread
+  constexpr int ROWB = 2 * D;        // bytes per K/V row
+  constexpr int CPR = D / 8;         // 16-byte chunks per row
+  constexpr int RPI = 64 / CPR;      // rows covered by one wavefront-wide copy instruction
+  constexpr int IPT = KT / RPI;      // copy instructions per K (or V) tile
+  constexpr int IPW = IPT / NW;      // ... per wavefront
+  constexpr int LPT = 2 * IPW;       // copies per wavefront per tile (K and V)
+  constexpr int TILEB = KT * ROWB;   // bytes of a K (or V) tile
+  constexpr int STAGEB = 2 * TILEB;  // K then V
   constexpr int NC = D / 16;         // 16-wide steps of the head dimension
   constexpr int ND = D / 32;         // 32-row tiles of O^T
+  static_assert(IPT % NW == 0, "tile copies must divide over the wavefronts");
+  static_assert((NS - 1) * LPT < 64, "outstanding copies must fit the vmcnt counter");
 
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  __bf16* Ks = reinterpret_cast<__bf16*>(smem);   // [2][KT][KSTR]
-  __bf16* Vs = Ks + 2 * KT * KSTR;                // [2][KT][VSTR]
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char*)smem;
 
   // ---- which work item: consecutive items stay on one XCD (one L2) ----
   const int pid = blockIdx.x;
@@ -118,8 +177,28 @@ __global__ __launch_bounds__(64 * NW) void pa_prefill_bf16_kernel(bf16_params p)
   // tiles of the diagonal block needed by any wavefront of this workgroup
   int last_task = chunk * NW + NW - 1;
   if (last_task > p.tasks - 1) last_task = p.tasks - 1;
-  int max_sl = (last_task / slices > (chunk * NW) / slices) ? slices - 1 : last_task % slices;
+  const int max_sl = (last_task / slices > (chunk * NW) / slices) ? slices - 1 : last_task % slices;
   const int subs_diag = (max_sl * QW + QW - 1) / KT + 1;
+
+  const __bf16* kbase = p.k + (((int64_t)b * p.hkv + kvh) * p.N) * D;
+  const __bf16* vbase = p.v + (((int64_t)b * p.hkv + kvh) * p.N) * D;
+
+  // ---- asynchronous tile copy: this wavefront's share of tile `tp` into ring stage `stage` ----
+  const int cp_row = lane / CPR, cp_chunk = lane % CPR;
+  auto issue_tile = [&](const tile_pos& tp, int stage) {
+    const int64_t key0 = (int64_t)tp.j * p.B + (int64_t)tp.u * KT;
+#pragma unroll
+    for (int x = 0; x < IPW; ++x) {
+      const int inst = wave * IPW + x;                 // rows RPI*inst .. +RPI-1 of the tile
+      const int row = RPI * inst + cp_row;
+      int64_t grow = key0 + row;
+      if (grow > p.N - 1) grow = p.N - 1;              // ragged tail: repeat the last row (it is masked, but must be finite)
+      const int64_t off = grow * D + ((cp_chunk ^ swz<D>(row)) << 3);
+      const uint32_t dst = lds0 + stage * STAGEB + inst * 1024;
+      async_copy16(kbase + off, __builtin_amdgcn_readfirstlane(dst));
+      async_copy16(vbase + off, __builtin_amdgcn_readfirstlane(dst + TILEB));
+    }
+  };
 
   // ---- Q^T fragments: lane = query column, 8 consecutive d per 16-wide step ----
   bf16x8 qf[CT][NC];
@@ -135,6 +214,33 @@ __global__ __launch_bounds__(64 * NW) void pa_prefill_bf16_kernel(bf16_params p)
     }
   }
 
+  // ---- fill the ring ----
+  __shared__ int s_list[LIST_CAP];
+  list_view Ls;
+  Ls.dense = p.dense != 0;
+  Ls.lds = s_list;
+  {
+    int n = p.dense ? i + 1 : p.kv_cnt[i];
+    if (!p.dense && n > p.max_k) n = p.max_k;
+    if (!p.dense && n > LIST_CAP) n = LIST_CAP;          // the host refuses longer rows
+    Ls.n = __builtin_amdgcn_readfirstlane(n);
+  }
+  if (!p.dense) {
+    for (int e = tid; e < Ls.n; e += 64 * NW) s_list[e] = p.kv_idx[(int64_t)i * p.max_k + e];
+    __syncthreads();
+  }
+  tile_pos cur = uniform(seek(Ls, i, 0));
+  tile_pos pre = cur;                 // the prefetch position runs NS-1 tiles ahead of the compute position
+  int issued = 0;
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s) {
+    if (pre.valid) {
+      issue_tile(pre, s);
+      pre = advance(Ls, i, pre, p.subs, subs_diag);
+      ++issued;
+    }
+  }
+
   f32x16 O[ND][CT];
 #pragma unroll
   for (int dt = 0; dt < ND; ++dt)
@@ -146,53 +252,38 @@ __global__ __launch_bounds__(64 * NW) void pa_prefill_bf16_kernel(bf16_params p)
 #pragma unroll
   for (int ct = 0; ct < CT; ++ct) { m_run[ct] = -INFINITY; l_run[ct] = 0.f; }
 
-  const __bf16* kbase = p.k + (((int64_t)b * p.hkv + kvh) * p.N) * D;
-  const __bf16* vbase = p.v + (((int64_t)b * p.hkv + kvh) * p.N) * D;
+  // per-lane pieces of the swizzled LDS addresses
+  const int k_sw = swz<D>(ln);                               // rows 32rt + ln share their low bits with ln
+  const int v_r4 = 4 * hh + ((lane & 15) >> 2);              // row of the first transposing read inside a 16-key step
+  const int v_x = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1); // chunk inside the 32-wide d tile
+  const int v_sw0 = swz<D>(v_r4), v_sw1 = swz<D>(v_r4 + 8);
 
-  uint4 kreg[CPT], vreg[CPT];
-  auto load_tile = [&](const tile_pos& tp) {
-    const int64_t key0 = (int64_t)tp.j * p.B + (int64_t)tp.u * KT;
-#pragma unroll
-    for (int x = 0; x < CPT; ++x) {
-      const int c = tid + x * NT;
-      const int row = c / CPR;
-      const bool ok = (CHUNKS % NT == 0 || c < CHUNKS) && (key0 + row) < p.N;
-      const int64_t off = key0 * D + (int64_t)c * 8;
-      kreg[x] = ok ? *reinterpret_cast<const uint4*>(kbase + off) : make_uint4(0, 0, 0, 0);
-      vreg[x] = ok ? *reinterpret_cast<const uint4*>(vbase + off) : make_uint4(0, 0, 0, 0);
-    }
-  };
-  auto store_tile = [&](int buf) {
-#pragma unroll
-    for (int x = 0; x < CPT; ++x) {
-      const int c = tid + x * NT;
-      if (CHUNKS % NT == 0 || c < CHUNKS) {
-        const int row = c / CPR, col = c % CPR;
-        *reinterpret_cast<uint4*>(Ks + (buf * KT + row) * KSTR + col * 8) = kreg[x];
-        *reinterpret_cast<uint4*>(Vs + (buf * KT + row) * VSTR + col * 8) = vreg[x];
-      }
-    }
-  };
+  // Q fragments and the first tiles must have arrived before the loop; waiting here, once, also tells
+  // the compiler that none of its own loads is outstanding inside the loop, so that it does not add
+  // full vmcnt(0) waits there (they would drain the asynchronous copies as well).
+  wait_vmcnt<0>();
 
-  const int n_list = list_len(p, i);
-  tile_pos cur = seek(p, i, n_list, 0);
-  if (cur.valid) {
-    load_tile(cur);
-    store_tile(0);
-  }
-  __syncthreads();
-  int buf = 0;
-
+  int t = 0;
   while (cur.valid) {
-    const tile_pos nxt = advance(p, i, n_list, cur, subs_diag);
-    if (nxt.valid) load_tile(nxt);
+    // tile t has landed once at most the younger tiles' copies are outstanding
+    const int pending = issued - (t + 1);
+    if (pending >= NS - 1) wait_vmcnt<(NS - 1) * LPT>();
+    else if (pending == 2 && NS > 3) wait_vmcnt<(NS > 3 ? 2 : 0) * LPT>();
+    else if (pending == 1 && NS > 2) wait_vmcnt<(NS > 2 ? 1 : 0) * LPT>();
+    else wait_vmcnt<0>();
+    __syncthreads();   // every wavefront's share is in LDS; everybody is done with the stage refilled below
+    if (pre.valid) {
+      issue_tile(pre, (t + NS - 1) % NS);
+      pre = advance(Ls, i, pre, p.subs, subs_diag);
+      ++issued;
+    }
 
     const bool diag = (cur.j == i);
     const int key_in_blk = cur.u * KT;
     // tiles of the diagonal block that start after this wavefront's last query are fully masked
     if (active && !(diag && key_in_blk > q_in_blk + QW - 1)) {
-      const __bf16* Kb = Ks + buf * KT * KSTR;
-      const __bf16* Vb = Vs + buf * KT * VSTR;
+      const unsigned char* Kb = smem + (t % NS) * STAGEB;
+      const unsigned char* Vb = Kb + TILEB;
 
       // ---- S^T = K Q^T ----
       f32x16 S[2][CT];
@@ -206,7 +297,7 @@ __global__ __launch_bounds__(64 * NW) void pa_prefill_bf16_kernel(bf16_params p)
       for (int c = 0; c < NC; ++c) {
 #pragma unroll
         for (int rt = 0; rt < 2; ++rt) {
-          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(Kb + (32 * rt + ln) * KSTR + 16 * c + 8 * hh);
+          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(Kb + (32 * rt + ln) * ROWB + (((2 * c + hh) ^ k_sw) << 4));
 #pragma unroll
           for (int ct = 0; ct < CT; ++ct)
             S[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ct][c], S[rt][ct], 0, 0, 0);
@@ -232,29 +323,36 @@ __global__ __launch_bounds__(64 * NW) void pa_prefill_bf16_kernel(bf16_params p)
         for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
           for (int r = 0; r < 16; ++r) mx = fmaxf(mx, S[rt][ct][r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run[ct], mx * p.c2);
-        const float alpha = __builtin_amdgcn_exp2f(m_run[ct] - m_new);
-        m_run[ct] = m_new;
+        mx = fmaxf(mx, __shfl_xor(mx, 32)) * p.c2;
+        // The reference point m of the exponentials need not be the exact running maximum: any m
+        // gives the same o and lse as long as exp2(s - m) stays in range.  It is raised only when a
+        // score exceeds it by more than RESCALE_TAU (p <= 2^tau), which makes the rescaling of O
+        // (64 multiplies per lane) a rare, wavefront-uniform branch instead of a per-tile cost.
+        const bool raise = mx > m_run[ct] + RESCALE_TAU;     // also true for the first tile (m = -inf)
+        if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+          const float m_new = raise ? mx : m_run[ct];
+          const float alpha = __builtin_amdgcn_exp2f(m_run[ct] - m_new);   // exp2(-inf) = 0 on the first tile
+          m_run[ct] = m_new;
+          l_run[ct] *= alpha;
+#pragma unroll
+          for (int dt = 0; dt < ND; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) O[dt][ct][r] *= alpha;
+        }
+        const float m_ref = m_run[ct];
         float rowsum = 0.f;
 #pragma unroll
         for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const float pv = __builtin_amdgcn_exp2f(fmaf(S[rt][ct][r], p.c2, -m_new));
+            const float pv = __builtin_amdgcn_exp2f(fmaf(S[rt][ct][r], p.c2, -m_ref));
             rowsum += pv;
             S[rt][ct][r] = pv;
           }
-        l_run[ct] = l_run[ct] * alpha + rowsum;
-#pragma unroll
-        for (int dt = 0; dt < ND; ++dt)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) O[dt][ct][r] *= alpha;
+        l_run[ct] += rowsum;
       }
 
       // ---- O^T += V^T P^T, 16 keys per step ----
-      const int vrow = 4 * hh + ((lane & 15) >> 2);
-      const int vcol = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
         const int rt = kk >> 1, r0 = 8 * (kk & 1);
@@ -265,9 +363,11 @@ __global__ __launch_bounds__(64 * NW) void pa_prefill_bf16_kernel(bf16_params p)
           for (int e = 0; e < 8; ++e) pf[ct][e] = (__bf16)S[rt][ct][r0 + e];
 #pragma unroll
         for (int dt = 0; dt < ND; ++dt) {
-          const __bf16* vp = Vb + (16 * kk + vrow) * VSTR + 32 * dt + vcol;
-          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp));
-          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp + 8 * VSTR));
+          const int cl = 4 * dt + v_x;
+          const unsigned char* vp0 = Vb + (16 * kk + v_r4) * ROWB + ((cl ^ v_sw0) << 4) + 8 * (lane & 1);
+          const unsigned char* vp1 = Vb + (16 * kk + v_r4 + 8) * ROWB + ((cl ^ v_sw1) << 4) + 8 * (lane & 1);
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp0));
+          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp1));
           const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
           const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
 #pragma unroll
@@ -277,11 +377,8 @@ __global__ __launch_bounds__(64 * NW) void pa_prefill_bf16_kernel(bf16_params p)
       }
     }
 
-    if (!nxt.valid) break;
-    store_tile(buf ^ 1);
-    __syncthreads();
-    buf ^= 1;
-    cur = nxt;
+    cur = advance(Ls, i, cur, p.subs, subs_diag);
+    ++t;
   }
 
   // ---- epilogue: register r of tile dt is d = 32dt + 8(r/4) + 4hh + r%4 ----
@@ -307,54 +404,45 @@ __global__ __launch_bounds__(64 * NW) void pa_prefill_bf16_kernel(bf16_params p)
   }
 }
 
-template <int D, int CT, int NW>
+template <int D, int CT, int NW, int NS>
 int launch(const bf16_params& p, hipStream_t stream) {
-  constexpr size_t lds = (size_t)2 * KT * ((D + 8) + (D + 32)) * sizeof(__bf16);
+  constexpr size_t lds = (size_t)NS * 2 * KT * 2 * D;
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pa_prefill_bf16_kernel<D, CT, NW>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pa_prefill_bf16_kernel<D, CT, NW, NS>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return pa_note_hip(e);
     attr_done = true;
   }
   const int64_t grid = (int64_t)p.per_xcd * 8;
-  hipLaunchKernelGGL((pa_prefill_bf16_kernel<D, CT, NW>), dim3((uint32_t)grid), dim3(64 * NW), lds, stream, p);
+  hipLaunchKernelGGL((pa_prefill_bf16_kernel<D, CT, NW, NS>), dim3((uint32_t)grid), dim3(64 * NW), lds, stream, p);
   return pa_note_hip(hipGetLastError());
-}
-
-template <int D, int CT>
-int launch_nw(const bf16_params& p, int nw, hipStream_t stream) {
-  if constexpr (CT == 1) {
-    if (nw == 8) return launch<D, 1, 8>(p, stream);
-  }
-  return launch<D, CT, 4>(p, stream);
 }
 
 }  // namespace
 
 int pa_launch_prefill_bf16(const pa_prefill_args& a) {
-  static const int env_ct = [] { const char* s = getenv("POWATTN_PREFILL_CT"); return s ? atoi(s) : 0; }();
-  const int ct = (env_ct == 1 || env_ct == 2) ? env_ct : 1;
+  constexpr int ct = 1;   // 32-query wavefronts, two per SIMD (64-query wavefronts measured slower)
 
   bf16_params p;
   p.q = (const __bf16*)a.q; p.k = (const __bf16*)a.k; p.v = (const __bf16*)a.v; p.o = (__bf16*)a.o; p.lse = a.lse;
   p.kv_cnt = a.kv_cnt; p.kv_idx = a.kv_idx; p.max_k = a.max_k; p.nb = a.nb; p.B = a.pat.block;
   p.hq = a.hq; p.hkv = a.hkv; p.G = a.hq / a.hkv; p.dense = (a.pat.flags & POWATTN_DENSE) ? 1 : 0;
   p.subs = p.B / KT;
+  if (!p.dense && a.max_k > LIST_CAP) return POWATTN_UNSUPPORTED;
   p.N = a.seq_len;
   p.c2 = a.scale * 1.44269504088896340736f;
   const int64_t tasks = (int64_t)p.G * p.B / (32 * ct);
   if (tasks > (1 << 20)) return POWATTN_UNSUPPORTED;
   p.tasks = (int32_t)tasks;
-  // 64-query wavefronts need the whole register file of a SIMD (one wavefront per SIMD, 4 per
-  // workgroup); 32-query wavefronts fit two per SIMD (8 per workgroup)
-  const int nw = (ct == 1 && p.tasks > 4) ? 8 : 4;
+  const int nw = p.tasks > 4 ? 8 : 4;
   p.chunks = (p.tasks + nw - 1) / nw;
   p.total_wg = (int64_t)a.batch * a.hkv * a.nb * p.chunks;
   const int64_t per_xcd = (p.total_wg + 7) / 8;
   if (per_xcd * 8 > 0x7fffffffLL) return POWATTN_UNSUPPORTED;
   p.per_xcd = (int32_t)per_xcd;
 
-  if (a.head_dim == 128) return ct == 2 ? launch_nw<128, 2>(p, nw, a.stream) : launch_nw<128, 1>(p, nw, a.stream);
-  return ct == 2 ? launch_nw<64, 2>(p, nw, a.stream) : launch_nw<64, 1>(p, nw, a.stream);
+  // ring of 4 stages: 128 KB of LDS at head_dim 128, 64 KB at head_dim 64
+  if (a.head_dim == 128) return nw == 8 ? launch<128, 1, 8, 4>(p, a.stream) : launch<128, 1, 4, 4>(p, a.stream);
+  return nw == 8 ? launch<64, 1, 8, 4>(p, a.stream) : launch<64, 1, 4, 4>(p, a.stream);
 }
