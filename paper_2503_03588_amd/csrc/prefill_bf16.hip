@@ -58,56 +58,12 @@ struct bf16_params {
   float c2;          // softmax scale * log2(e)
 };
 
-// Position inside the flattened sequence of 64-key tiles of one query block.
-struct tile_pos {
-  int t;   // list position
-  int j;   // key block
-  int u;   // 64-key tile inside the block
-  bool valid;
-};
-
-// The block list of one query block is copied into LDS once; a lookup is then an LDS read made
-// wavefront-uniform with v_readfirstlane.  Going through LDS matters: a lookup from global memory
-// inside the tile loop would be a vector load, and waiting for it would also wait for every
-// asynchronous tile copy in flight.
-constexpr int LIST_CAP = 1024;   // longest block list the kernel accepts (the dense list is implicit)
-
-struct list_view {
-  const int* lds;   // the row in LDS
-  int n;            // entries
-  bool dense;
-};
-
-__device__ __forceinline__ int list_at(const list_view& L, int t) {
-  return L.dense ? t : __builtin_amdgcn_readfirstlane(L.lds[t]);
-}
-
-// first list position >= t whose entry is a causal block, or n
-__device__ __forceinline__ tile_pos seek(const list_view& L, int i, int t) {
-  tile_pos r;
-  r.u = 0;
-  for (; t < L.n; ++t) {
-    const int j = list_at(L, t);
-    if (j >= 0 && j <= i) { r.t = t; r.j = j; r.valid = true; return r; }
-  }
-  r.t = L.n; r.j = 0; r.valid = false;
-  return r;
-}
-
-// Positions are the same in every lane; saying so keeps the loop control on the scalar unit.
-__device__ __forceinline__ tile_pos uniform(tile_pos r) {
-  r.t = __builtin_amdgcn_readfirstlane(r.t);
-  r.j = __builtin_amdgcn_readfirstlane(r.j);
-  r.u = __builtin_amdgcn_readfirstlane(r.u);
-  r.valid = __builtin_amdgcn_readfirstlane((int)r.valid) != 0;
-  return r;
-}
-
-__device__ __forceinline__ tile_pos advance(const list_view& L, int i, tile_pos c, int subs, int subs_diag) {
-  const int lim = (c.j == i) ? subs_diag : subs;
-  if (c.u + 1 < lim) { c.u += 1; return uniform(c); }
-  return uniform(seek(L, i, c.t + 1));
-}
+// The work of one query block is a sequence of 64-key tiles.  For a block list it is written once,
+// as the first key of every tile, into a table in LDS (a lookup is then an LDS read made wavefront-
+// uniform with v_readfirstlane); for the dense list it is implicit.  Keeping memory out of the tile
+// loop matters: a vector load there would have to be waited for together with every asynchronous
+// tile copy in flight.
+constexpr int TILE_CAP = 4096;   // tiles per query block with an explicit list (16 KB of LDS)
 
 // Asynchronous 16-byte-per-lane copy global -> LDS: lane l's data lands at lds_off + 16*l.
 // Written as inline assembly on purpose: the compiler then does not pair every later LDS read
@@ -148,7 +104,7 @@ void pa_prefill_bf16_kernel(bf16_params p) {
   constexpr int NC = D / 16;         // 16-wide steps of the head dimension
   constexpr int ND = D / 32;         // 32-row tiles of O^T
   static_assert(IPT % NW == 0, "tile copies must divide over the wavefronts");
-  static_assert((NS - 1) * LPT < 64, "outstanding copies must fit the vmcnt counter");
+  static_assert(NS >= 3 && NS <= 4 && (NS - 1) * LPT < 64, "outstanding copies must fit the vmcnt counter");
 
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char*)smem;
@@ -185,8 +141,7 @@ void pa_prefill_bf16_kernel(bf16_params p) {
 
   // ---- asynchronous tile copy: this wavefront's share of tile `tp` into ring stage `stage` ----
   const int cp_row = lane / CPR, cp_chunk = lane % CPR;
-  auto issue_tile = [&](const tile_pos& tp, int stage) {
-    const int64_t key0 = (int64_t)tp.j * p.B + (int64_t)tp.u * KT;
+  auto issue_tile = [&](int64_t key0, int stage) {
 #pragma unroll
     for (int x = 0; x < IPW; ++x) {
       const int inst = wave * IPW + x;                 // rows RPI*inst .. +RPI-1 of the tile
@@ -215,31 +170,37 @@ void pa_prefill_bf16_kernel(bf16_params p) {
   }
 
   // ---- fill the ring ----
-  __shared__ int s_list[LIST_CAP];
-  list_view Ls;
-  Ls.dense = p.dense != 0;
-  Ls.lds = s_list;
-  {
-    int n = p.dense ? i + 1 : p.kv_cnt[i];
-    if (!p.dense && n > p.max_k) n = p.max_k;
-    if (!p.dense && n > LIST_CAP) n = LIST_CAP;          // the host refuses longer rows
-    Ls.n = __builtin_amdgcn_readfirstlane(n);
-  }
-  if (!p.dense) {
-    for (int e = tid; e < Ls.n; e += 64 * NW) s_list[e] = p.kv_idx[(int64_t)i * p.max_k + e];
-    __syncthreads();
-  }
-  tile_pos cur = uniform(seek(Ls, i, 0));
-  tile_pos pre = cur;                 // the prefetch position runs NS-1 tiles ahead of the compute position
-  int issued = 0;
-#pragma unroll
-  for (int s = 0; s < NS - 1; ++s) {
-    if (pre.valid) {
-      issue_tile(pre, s);
-      pre = advance(Ls, i, pre, p.subs, subs_diag);
-      ++issued;
+  __shared__ int s_tile[TILE_CAP];     // first key of tile t (explicit lists only)
+  __shared__ int s_ntiles;
+  const int64_t blk0 = (int64_t)i * p.B;   // first key of the diagonal block
+  int n_tiles;
+  if (p.dense) {
+    n_tiles = i * p.subs + subs_diag;      // blocks 0..i-1 in full, then the needed part of block i
+  } else {
+    if (tid == 0) {
+      int n = p.kv_cnt[i];
+      if (n > p.max_k) n = p.max_k;
+      int w = 0;
+      for (int e = 0; e < n; ++e) {
+        const int j = p.kv_idx[(int64_t)i * p.max_k + e];
+        if (j < 0 || j > i) continue;                       // padding, or not causal: skipped
+        const int lim = (j == i) ? subs_diag : p.subs;
+        for (int u = 0; u < lim && w < TILE_CAP; ++u) s_tile[w++] = j * p.B + u * KT;
+      }
+      s_ntiles = w;
     }
+    __syncthreads();
+    n_tiles = s_ntiles;
   }
+  n_tiles = __builtin_amdgcn_readfirstlane(n_tiles);
+  auto tile_key0 = [&](int t) -> int {       // wavefront-uniform
+    return p.dense ? t * KT : __builtin_amdgcn_readfirstlane(s_tile[t]);
+  };
+
+  // ---- fill the ring: the copies run NS-1 tiles ahead of the compute ----
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s)
+    if (s < n_tiles) issue_tile(tile_key0(s), s);
 
   f32x16 O[ND][CT];
 #pragma unroll
@@ -252,38 +213,46 @@ void pa_prefill_bf16_kernel(bf16_params p) {
 #pragma unroll
   for (int ct = 0; ct < CT; ++ct) { m_run[ct] = -INFINITY; l_run[ct] = 0.f; }
 
-  // per-lane pieces of the swizzled LDS addresses
-  const int k_sw = swz<D>(ln);                               // rows 32rt + ln share their low bits with ln
-  const int v_r4 = 4 * hh + ((lane & 15) >> 2);              // row of the first transposing read inside a 16-key step
-  const int v_x = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1); // chunk inside the 32-wide d tile
-  const int v_sw0 = swz<D>(v_r4), v_sw1 = swz<D>(v_r4 + 8);
+  // Per-lane byte offsets of the swizzled LDS reads inside a stage, computed once: the XOR cannot
+  // be folded into an instruction's immediate offset, the row steps (32 rows of K, 16 and 8 rows of V)
+  // can.
+  uint32_t k_off[NC];                 // K fragment of d-step c, row ln
+  {
+    const int sw = swz<D>(ln);        // rows 32rt + ln share their low bits with ln
+#pragma unroll
+    for (int c = 0; c < NC; ++c) k_off[c] = ln * ROWB + (((2 * c + hh) ^ sw) << 4);
+  }
+  uint32_t v_off0[ND], v_off1[ND];    // the two transposing reads of d tile dt, 16-key step 0
+  {
+    const int r4 = 4 * hh + ((lane & 15) >> 2);              // row of the first read inside a 16-key step
+    const int x = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1); // chunk inside the 32-wide d tile
+#pragma unroll
+    for (int dt = 0; dt < ND; ++dt) {
+      v_off0[dt] = TILEB + r4 * ROWB + (((4 * dt + x) ^ swz<D>(r4)) << 4) + 8 * (lane & 1);
+      v_off1[dt] = TILEB + (r4 + 8) * ROWB + (((4 * dt + x) ^ swz<D>(r4 + 8)) << 4) + 8 * (lane & 1);
+    }
+  }
 
   // Q fragments and the first tiles must have arrived before the loop; waiting here, once, also tells
   // the compiler that none of its own loads is outstanding inside the loop, so that it does not add
   // full vmcnt(0) waits there (they would drain the asynchronous copies as well).
   wait_vmcnt<0>();
 
-  int t = 0;
-  while (cur.valid) {
+  for (int t = 0; t < n_tiles; ++t) {
     // tile t has landed once at most the younger tiles' copies are outstanding
-    const int pending = issued - (t + 1);
-    if (pending >= NS - 1) wait_vmcnt<(NS - 1) * LPT>();
-    else if (pending == 2 && NS > 3) wait_vmcnt<(NS > 3 ? 2 : 0) * LPT>();
-    else if (pending == 1 && NS > 2) wait_vmcnt<(NS > 2 ? 1 : 0) * LPT>();
+    const int younger = n_tiles - 1 - t < NS - 2 ? n_tiles - 1 - t : NS - 2;
+    if (younger >= 2 && NS > 3) wait_vmcnt<(NS > 3 ? 2 : 0) * LPT>();
+    else if (younger == 1 && NS > 2) wait_vmcnt<(NS > 2 ? 1 : 0) * LPT>();
     else wait_vmcnt<0>();
     __syncthreads();   // every wavefront's share is in LDS; everybody is done with the stage refilled below
-    if (pre.valid) {
-      issue_tile(pre, (t + NS - 1) % NS);
-      pre = advance(Ls, i, pre, p.subs, subs_diag);
-      ++issued;
-    }
+    if (t + NS - 1 < n_tiles) issue_tile(tile_key0(t + NS - 1), (t + NS - 1) % NS);
 
-    const bool diag = (cur.j == i);
-    const int key_in_blk = cur.u * KT;
+    const int key0 = tile_key0(t);
+    const bool diag = key0 >= blk0;
+    const int key_in_blk = key0 - (int)blk0;
     // tiles of the diagonal block that start after this wavefront's last query are fully masked
     if (active && !(diag && key_in_blk > q_in_blk + QW - 1)) {
-      const unsigned char* Kb = smem + (t % NS) * STAGEB;
-      const unsigned char* Vb = Kb + TILEB;
+      const unsigned char* Sb = smem + (t % NS) * STAGEB;
 
       // ---- S^T = K Q^T ----
       f32x16 S[2][CT];
@@ -297,7 +266,7 @@ void pa_prefill_bf16_kernel(bf16_params p) {
       for (int c = 0; c < NC; ++c) {
 #pragma unroll
         for (int rt = 0; rt < 2; ++rt) {
-          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(Kb + (32 * rt + ln) * ROWB + (((2 * c + hh) ^ k_sw) << 4));
+          const bf16x8 kf = *reinterpret_cast<const bf16x8*>(Sb + k_off[c] + rt * (32 * ROWB));
 #pragma unroll
           for (int ct = 0; ct < CT; ++ct)
             S[rt][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ct][c], S[rt][ct], 0, 0, 0);
@@ -363,11 +332,8 @@ void pa_prefill_bf16_kernel(bf16_params p) {
           for (int e = 0; e < 8; ++e) pf[ct][e] = (__bf16)S[rt][ct][r0 + e];
 #pragma unroll
         for (int dt = 0; dt < ND; ++dt) {
-          const int cl = 4 * dt + v_x;
-          const unsigned char* vp0 = Vb + (16 * kk + v_r4) * ROWB + ((cl ^ v_sw0) << 4) + 8 * (lane & 1);
-          const unsigned char* vp1 = Vb + (16 * kk + v_r4 + 8) * ROWB + ((cl ^ v_sw1) << 4) + 8 * (lane & 1);
-          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp0));
-          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(vp1));
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(Sb + v_off0[dt] + kk * (16 * ROWB)));
+          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(Sb + v_off1[dt] + kk * (16 * ROWB)));
           const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
           const bf16x8 vf = __builtin_bit_cast(bf16x8, both);
 #pragma unroll
@@ -377,8 +343,6 @@ void pa_prefill_bf16_kernel(bf16_params p) {
       }
     }
 
-    cur = advance(Ls, i, cur, p.subs, subs_diag);
-    ++t;
   }
 
   // ---- epilogue: register r of tile dt is d = 32dt + 8(r/4) + 4hh + r%4 ----
@@ -429,7 +393,8 @@ int pa_launch_prefill_bf16(const pa_prefill_args& a) {
   p.kv_cnt = a.kv_cnt; p.kv_idx = a.kv_idx; p.max_k = a.max_k; p.nb = a.nb; p.B = a.pat.block;
   p.hq = a.hq; p.hkv = a.hkv; p.G = a.hq / a.hkv; p.dense = (a.pat.flags & POWATTN_DENSE) ? 1 : 0;
   p.subs = p.B / KT;
-  if (!p.dense && a.max_k > LIST_CAP) return POWATTN_UNSUPPORTED;
+  if (!p.dense && (int64_t)a.max_k * p.subs > TILE_CAP) return POWATTN_UNSUPPORTED;
+  if (a.seq_len > 0x7fffffffLL - 1024) return POWATTN_UNSUPPORTED;   // key positions are kept in 32 bits
   p.N = a.seq_len;
   p.c2 = a.scale * 1.44269504088896340736f;
   const int64_t tasks = (int64_t)p.G * p.B / (32 * ct);
