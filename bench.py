@@ -27,8 +27,8 @@ PEAK_HBM_GBS = 8000.0            # MI355X HBM3E peak
 
 # HBM traffic of one prefill launch at the default workload, from rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE runs scaled by a copy kernel of known size (profiles/prefill_bf16_128k_pmc.md).
-# None until measured for the current kernel.
-PREFILL_TRAFFIC_BYTES = None
+# read 4.33 GB + written 1.09 GB per launch.
+PREFILL_TRAFFIC_BYTES = 5.43e9
 
 
 def main():
