@@ -22,6 +22,9 @@ HIPCC_FLAGS = [
     "-Wall", "-Wno-unused-function",
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # the prefill step is one fully unrolled instruction stream of 32 matrix instructions; the default size
+    # limit for loops with an unroll pragma is too small for it
+    "-mllvm", "-pragma-unroll-threshold=200000",
 ]
 
 

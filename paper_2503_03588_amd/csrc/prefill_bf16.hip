@@ -2,12 +2,16 @@
 // key blocks listed for each query block (Algorithm 1 lifted to blocks), as a
 // flash-style online softmax with fp32 accumulation.
 //
-// Decomposition.  A workgroup owns one (batch, KV head, query block) and up to
-// NW "tasks"; a task is one query head of the GQA group x 32 consecutive query
-// tokens, and belongs to one wavefront.  All wavefronts of the workgroup share
-// the K/V tiles staged in LDS, which is what lifts the arithmetic intensity: a
-// 64-key tile is read from HBM/L2 once per workgroup and used by every head of
-// the group.
+// Decomposition.  A work item is one (batch, KV head, query block) and up to NW
+// "tasks"; a task is one query head of the GQA group x 32 consecutive query
+// tokens, and belongs to one wavefront.  A workgroup is persistent: it walks
+// through its share of the work items, and the K/V tile stream, the block list
+// and the Q rows of the next item are fetched while the current one computes
+// (a query block attends only a dozen key blocks, so an item lasts some tens of
+// microseconds and three dependent trips to memory at its start would cost a
+// sixth of it).  All wavefronts of the workgroup share the K/V tiles staged in
+// LDS, which is what lifts the arithmetic intensity: a 64-key tile is read from
+// HBM/L2 once per workgroup and used by every head of the group.
 //
 // Per 64-key tile a wavefront computes, with v_mfma_f32_32x32x16_bf16,
 //   S^T = K Q^T   (A = K rows from LDS, B = Q^T held in registers)
@@ -27,15 +31,23 @@
 // second half of S(t), and the 16 matrix instructions of O += P(t) V(t) next to
 // the row maximum of S(t+1) and the exponentials of its first half.  The whole
 // iteration is one basic block (the causal mask is a template variant, the
-// rescaling of O a rare branch at its end) and scheduling groups spell out the
-// interleaving.
+// rescaling of O a rare branch at its end), written in the order it is to be
+// issued, with a scheduling barrier after every matrix instruction.  A SIMD
+// issues about one instruction of any kind every 4 to 5 cycles, whichever of its
+// wavefronts it comes from, and a matrix instruction keeps the matrix core busy
+// for 32: the step is bound by its instruction count (about ten per matrix
+// instruction), so waits are shared by pairs of matrix instructions, addresses
+// are immediates and the tile copies ride along in the same stream.
 //
 // Memory pipeline.  K/V tiles travel global -> LDS asynchronously
 // (global_load_lds_dwordx4, no registers in between) into a ring of NS stages;
 // a wavefront waits on its own loads with s_waitcnt vmcnt(n) and one barrier
-// per tile makes the stage visible and frees the oldest one.  The asynchronous
-// copy cannot pad rows, so bank conflicts are avoided by a XOR swizzle of the
-// 16-byte chunk index with the row index, applied on the global-address side.
+// per tile makes the stage visible and frees the oldest one.  One copy
+// instruction moves 1 KB (RPI consecutive rows); inside that kilobyte the lanes
+// are permuted so that it lands chunk-major (16-byte chunk c of row a at slot
+// c*RPI + a), and consecutive kilobytes are 16*RPI bytes apart.  Fragment reads
+// are then free of bank conflicts and every fragment address is one per-lane
+// base plus an immediate offset.
 #include <math.h>
 #include <stdlib.h>
 #include <type_traits>
@@ -66,7 +78,8 @@ struct bf16_params {
   int32_t subs;      // 64-key tiles per block
   int32_t tasks;     // G * B / 32
   int32_t chunks;    // workgroups per (batch, kv head, query block)
-  int32_t per_xcd;   // workgroups per XCD partition
+  int32_t per_xcd;   // work items per XCD partition
+  int32_t chain;     // items may be chained in persistent workgroups
   int64_t total_wg;
   int64_t N;
   float c2;          // softmax scale * log2(e)
@@ -89,20 +102,18 @@ __device__ __forceinline__ void async_copy16(const void* sbase, uint32_t voff, u
   asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_off) : "memory");
 }
 
+// a wavefront-uniform pointer, forced into scalar registers
+template <typename T>
+__device__ __forceinline__ const T* uniform_ptr(const T* ptr) {
+  const uint64_t u = (uint64_t)(uintptr_t)ptr;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)u), hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
+  return (const T*)(uintptr_t)(((uint64_t)hi << 32) | lo);
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {   // s_waitcnt vmcnt(N) only
   static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
   __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
-}
-
-// XOR swizzle of the 16-byte chunk index inside a row, as a function of the row's low bits.
-// D = 128 (16 chunks per row): any 16 consecutive rows map one chunk column onto 16 different
-// bank groups (K fragment reads), and 4 consecutive rows x 4 consecutive chunks map onto 16
-// different bank groups (transposing V reads).  D = 64 (8 chunks per row, two rows per 256 B).
-template <int D>
-__device__ __forceinline__ int swz(int row) {
-  if (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);
-  return (row >> 1) & 7;
 }
 
 template <int D, int NW, int NS>
@@ -114,176 +125,247 @@ void pa_prefill_bf16_kernel(bf16_params p) {
   constexpr int IPT = KT / RPI;      // copy instructions per K (or V) tile
   constexpr int IPW = IPT / NW;      // ... per wavefront
   constexpr int LPT = 2 * IPW;       // copies per wavefront per tile (K and V)
-  constexpr int TILEB = KT * ROWB;   // bytes of a K (or V) tile
+  constexpr int SRB = 1024 + 16 * RPI;       // LDS distance between the kilobytes of consecutive copy instructions
+  constexpr int TILEB = IPT * SRB;   // LDS bytes of a K (or V) tile
   constexpr int STAGEB = 2 * TILEB;  // K then V
   constexpr int NC = D / 16;         // 16-wide steps of the head dimension
   constexpr int ND = D / 32;         // 32-row tiles of O^T
+  constexpr int MIN_STEPS = NS - 1;  // an item that is followed by another one lasts at least this many steps
   static_assert(IPT % NW == 0, "tile copies must divide over the wavefronts");
-  static_assert(NS == 4 && (NS - 1) * LPT < 64, "outstanding copies must fit the vmcnt counter");
+  static_assert(NS == 4 && (NS - 1) * LPT + NC + 1 < 64, "outstanding copies must fit the vmcnt counter");
 
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char*)smem;
+  __shared__ int s_tile[TILE_CAP];     // first key of every tile of an item; two halves when items are chained
+  __shared__ int s_cnt[2][2];          // per table: tiles in total, tiles before the diagonal block
+  __shared__ int s_raw[NW][64];        // per wavefront: the raw list row of the item after next (entry 63 = its length)
 
-  // ---- which work item: consecutive items stay on one XCD (one L2) ----
   const int pid = blockIdx.x;
-  const int slot = pid >> 3;
-  int64_t L = (int64_t)(pid & 7) * p.per_xcd + slot;
-  if (slot >= p.per_xcd || L >= p.total_wg) return;
-  const int chunk = (int)(L % p.chunks); L /= p.chunks;
-  const int i = p.nb - 1 - (int)(L % p.nb); L /= p.nb;   // longest rows first (matters for the dense list)
-  const int kvh = (int)(L % p.hkv);
-  const int b = (int)(L / p.hkv);
-
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform, and the compiler knows it
   const int ln = lane & 31, hh = lane >> 5;
   const int slices = p.B / QW;
-  const int task = chunk * NW + wave;
-  const bool active = task < p.tasks;
-  const int g = active ? task / slices : 0;
-  const int sl = active ? task % slices : 0;
-  const int h = kvh * p.G + g;
-  const int q_in_blk = sl * QW;                       // first query of this wavefront inside the block
-  const int64_t q0 = (int64_t)i * p.B + q_in_blk;
 
-  // tiles of the diagonal block needed by any wavefront of this workgroup
-  int last_task = chunk * NW + NW - 1;
-  if (last_task > p.tasks - 1) last_task = p.tasks - 1;
-  const int max_sl = (last_task / slices > (chunk * NW) / slices) ? slices - 1 : last_task % slices;
-  const int subs_diag = (max_sl * QW + QW - 1) / KT + 1;
+  // ---- this workgroup's work items: item k is number xcd*per_xcd + cuslot + nslots*k of the launch, so that
+  // the workgroups of one XCD (one L2) work on neighbouring query blocks at any time ----
+  const int xcd = pid & 7, cuslot = pid >> 3, nslots = (int)(gridDim.x >> 3);
+  int n_items = 0;
+  {
+    int64_t lim = p.total_wg - (int64_t)xcd * p.per_xcd;
+    if (lim > p.per_xcd) lim = p.per_xcd;
+    if (lim > cuslot) n_items = (int)((lim - cuslot + nslots - 1) / nslots);
+  }
+  if (n_items == 0) return;
+  const bool chained = n_items > 1;    // tables in halves, list rows prefetched
+  const int tab_half = chained ? TILE_CAP / 2 : 0;
 
-  const __bf16* kbase = p.k + (((int64_t)b * p.hkv + kvh) * p.N) * D;
-  const __bf16* vbase = p.v + (((int64_t)b * p.hkv + kvh) * p.N) * D;
+  // Items are numbered L = ((b*hkv + kvh)*nb + r)*chunks + chunk with r counting query blocks from the last one
+  // down (longest rows first, which matters for the dense list).  The first item is decoded by division, the
+  // following ones by adding the stride nslots digit by digit with carries: all scalar, no division in the loop.
+  struct item_t { int chunk, r, kvh, b, i, subs_diag; };
+  auto finish_item = [&](item_t& it) {
+    it.i = p.nb - 1 - it.r;
+    // tiles of the diagonal block needed by any wavefront of the item
+    int last_task = it.chunk * NW + NW - 1;
+    if (last_task > p.tasks - 1) last_task = p.tasks - 1;
+    const int max_sl = (last_task / slices > (it.chunk * NW) / slices) ? slices - 1 : last_task % slices;
+    it.subs_diag = (max_sl * QW + QW - 1) / KT + 1;
+  };
+  auto digits = [&](uint32_t L) -> item_t {
+    item_t it;
+    it.chunk = (int)(L % (uint32_t)p.chunks); L /= (uint32_t)p.chunks;
+    it.r = (int)(L % (uint32_t)p.nb); L /= (uint32_t)p.nb;
+    it.kvh = (int)(L % (uint32_t)p.hkv);
+    it.b = (int)(L / (uint32_t)p.hkv);
+    it.i = 0; it.subs_diag = 0;
+    return it;
+  };
+  const item_t stride = digits((uint32_t)nslots);
+  auto next_item = [&](const item_t& cur) -> item_t {
+    item_t it = cur;
+    it.chunk += stride.chunk; if (it.chunk >= p.chunks) { it.chunk -= p.chunks; ++it.r; }
+    it.r += stride.r;         if (it.r >= p.nb) { it.r -= p.nb; ++it.kvh; }
+    it.kvh += stride.kvh;     if (it.kvh >= p.hkv) { it.kvh -= p.hkv; ++it.b; }
+    it.b += stride.b;
+    finish_item(it);
+    return it;
+  };
+  item_t it = stride, it1 = stride, it2 = stride;   // the current item, the next one, the one after (set below)
+
+  // ---- tile tables (explicit lists only) ----
+  // Writes the table of an item from its list row: lane e holds entry e (j), n entries in all; the tiles of the
+  // blocks before the diagonal one in list order (ranks by a prefix count over the lanes), then the diagonal ones.
+  // Called by the first wavefront, once per 64 entries.
+  auto table_rows = [&](int tab, const item_t& it, int j, int& blocks, bool& has_diag) {
+    const bool valid = j >= 0 && j < it.i;                  // not padding, causal, not the diagonal block
+    const uint64_t vm = __builtin_amdgcn_ballot_w64(valid);
+    has_diag = has_diag || __builtin_amdgcn_ballot_w64(j == it.i) != 0;
+    const int rank = blocks + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(vm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)vm, 0));
+    if (valid)
+      for (int u = 0; u < p.subs; ++u) s_tile[tab * tab_half + rank * p.subs + u] = j * p.B + u * KT;
+    blocks += __builtin_popcountll(vm);
+  };
+  auto table_finish = [&](int tab, const item_t& it, int blocks, bool has_diag) {
+    int w = blocks * p.subs;
+    if (lane == 0) s_cnt[tab][1] = w;
+    if (has_diag) {
+      if (lane < it.subs_diag) s_tile[tab * tab_half + w + lane] = it.i * p.B + lane * KT;
+      w += it.subs_diag;
+    }
+    if (lane == 0) s_cnt[tab][0] = w;
+  };
+  auto table_from_memory = [&](int tab, const item_t& it) {          // first wavefront
+    int n = p.kv_cnt[it.i];
+    if (n > p.max_k) n = p.max_k;
+    n = __builtin_amdgcn_readfirstlane(n);
+    int blocks = 0;
+    bool has_diag = false;
+    for (int base = 0; base < n; base += 64) {
+      const int e = base + lane;
+      const int j = e < n ? p.kv_idx[(int64_t)it.i * p.max_k + e] : -1;
+      table_rows(tab, it, j, blocks, has_diag);
+    }
+    table_finish(tab, it, blocks, has_diag);
+  };
+  auto table_from_row = [&](int tab, const item_t& it) {             // first wavefront; row copied earlier into s_raw[0]
+    int n = __builtin_amdgcn_readfirstlane(s_raw[0][63]);
+    if (n > p.max_k) n = p.max_k;
+    const int raw = s_raw[0][lane];
+    const int j = lane < n ? raw : -1;
+    int blocks = 0;
+    bool has_diag = false;
+    table_rows(tab, it, j, blocks, has_diag);
+    table_finish(tab, it, blocks, has_diag);
+  };
+  // Asynchronous copy of the list row of item k into this wavefront's s_raw (every wavefront issues it, so
+  // that all of them count the same number of outstanding copies; only the first one's copy is read).
+  auto copy_row = [&](const item_t& it) {
+    const int32_t* src = reinterpret_cast<const int32_t*>(p.k);      // dense: a dummy 4-byte read
+    if (!p.dense) {
+      const int e = lane < p.max_k ? lane : p.max_k - 1;
+      src = lane == 63 ? p.kv_cnt + it.i : p.kv_idx + (int64_t)it.i * p.max_k + e;
+    }
+    const uint32_t dst = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int*)&s_raw[0][0] + wave * 256;
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" ::"v"(src), "s"(__builtin_amdgcn_readfirstlane(dst)) : "memory");
+  };
 
   // ---- asynchronous tile copy: this wavefront's share of the tile starting at key0 into a ring stage ----
-  // The tile's base address is scalar; a lane adds the byte offset of its row and (swizzled) chunk.
-  const int cp_row = lane / CPR, cp_chunk = lane % CPR;
-  uint32_t cp_cb[IPW];                                 // swizzled chunk, in bytes, of copy instruction x
-#pragma unroll
-  for (int x = 0; x < IPW; ++x) cp_cb[x] = (uint32_t)((cp_chunk ^ swz<D>(RPI * (wave * IPW + x) + cp_row)) << 4);
-  auto issue_tile = [&](int key0, int stage) {
+  // The tile's base address is scalar; a lane adds the byte offset of its row and chunk.
+  const int cp_row = lane % RPI, cp_chunk = lane / RPI;   // lane l carries chunk l/RPI of row l%RPI of its kilobyte
+  // A fill is prepared once (scalar part) and issued as LPT separate copies, so that a step can spread them
+  // over its matrix instructions instead of queueing all wavefronts' copies behind one another after the barrier.
+  const __bf16* f_kt = p.k;
+  const __bf16* f_vt = p.v;
+  int f_lim = 0;
+  uint32_t f_dst = 0;
+  auto fill_prep = [&](const __bf16* kbase, const __bf16* vbase, int key0, int stage) {
     // ragged tail: rows beyond the sequence repeat its last row (they are masked, but must be finite)
     const int last = (int)p.N - 1;
     const int k0 = key0 < last ? key0 : last;
-    const int lim = last - k0;
-    const __bf16* kt = kbase + (int64_t)k0 * D;
-    const __bf16* vt = vbase + (int64_t)k0 * D;
+    f_lim = last - k0;
+    // (scalar values may live in vector registers when scalar registers are short: pin the bases down)
+    f_kt = uniform_ptr(kbase + (int64_t)k0 * D);
+    f_vt = uniform_ptr(vbase + (int64_t)k0 * D);
+    f_dst = lds0 + stage * STAGEB;
+  };
+  auto fill_part = [&](int j) {                        // copy j of LPT: instruction x = j/2 of this wavefront, K then V
+    const int inst = wave * IPW + (j >> 1);            // rows RPI*inst .. +RPI-1 of the tile
+    int row = RPI * inst + cp_row;
+    row = row < f_lim ? row : f_lim;
+    const uint32_t voff = (uint32_t)row * ROWB + (cp_chunk << 4);
+    const uint32_t dst = f_dst + inst * SRB + (j & 1) * TILEB;
+    async_copy16((j & 1) ? f_vt : f_kt, voff, __builtin_amdgcn_readfirstlane(dst));
+  };
+
+  // ---- the tile stream: a cursor runs NS-1 fills ahead of the compute, across item boundaries ----
+  // An item that has a successor lasts at least MIN_STEPS steps (short rows are padded with fills that nobody
+  // reads), so the cursor is never more than one item ahead and two tables are enough.
+  int c_k = 0, c_pos = 0, c_ntiles = 0, c_steps = 0, c_stage = 0;
+  const __bf16* c_kb = p.k;
+  const __bf16* c_vb = p.v;
+  auto cursor_enter = [&](int k, const item_t& it) {
+    c_k = k; c_pos = 0;
+    c_ntiles = p.dense ? it.i * p.subs + it.subs_diag : __builtin_amdgcn_readfirstlane(s_cnt[k & 1][0]);
+    c_steps = (k + 1 < n_items && c_ntiles < MIN_STEPS) ? MIN_STEPS : c_ntiles;
+    c_kb = p.k + (((int64_t)it.b * p.hkv + it.kvh) * p.N) * D;
+    c_vb = p.v + (((int64_t)it.b * p.hkv + it.kvh) * p.N) * D;
+  };
+  // Prepares the next fill of the stream.  After the end of the stream the fills go on, re-reading the first
+  // tile of the last item into stages nobody reads: every step then issues the same number of copies, and
+  // the waits can count them.
+  auto next_fill = [&]() {
+    if (c_pos >= c_steps && c_k + 1 < n_items)
+      cursor_enter(c_k + 1, it1);      // the cursor is never more than one item ahead of the compute
+    int key0 = 0;
+    if (c_pos < c_ntiles) key0 = p.dense ? c_pos * KT : __builtin_amdgcn_readfirstlane(s_tile[(c_k & 1) * tab_half + c_pos]);
+    fill_prep(c_kb, c_vb, key0, c_stage);
+    c_stage = c_stage == NS - 1 ? 0 : c_stage + 1;
+    ++c_pos;
+  };
+  auto fill_all = [&]() {
 #pragma unroll
-    for (int x = 0; x < IPW; ++x) {
-      const int inst = wave * IPW + x;                 // rows RPI*inst .. +RPI-1 of the tile
-      int row = RPI * inst + cp_row;
-      row = row < lim ? row : lim;
-      const uint32_t voff = (uint32_t)row * ROWB + cp_cb[x];
-      const uint32_t dst = lds0 + stage * STAGEB + inst * 1024;
-      async_copy16(kt, voff, __builtin_amdgcn_readfirstlane(dst));
-      async_copy16(vt, voff, __builtin_amdgcn_readfirstlane(dst + TILEB));
-    }
+    for (int j = 0; j < LPT; ++j) fill_part(j);
   };
 
   // ---- Q^T fragments: lane = query column, 8 consecutive d per 16-wide step ----
   bf16x8 qf[NC];
-  {
-    const __bf16* qbase = p.q + (((int64_t)b * p.hq + h) * p.N) * D;
-    const int64_t tok = q0 + ln;
-    const bool ok = active && tok < p.N;
+  auto load_q = [&](const item_t& it) {
+    const int task = it.chunk * NW + wave;
+    const bool act = task < p.tasks;
+    const int g = act ? task / slices : 0, sl = act ? task % slices : 0;
+    const int64_t tok = (int64_t)it.i * p.B + sl * QW + ln;
+    const __bf16* qrow = p.q + (((int64_t)it.b * p.hq + it.kvh * p.G + g) * p.N + tok) * D;
+    const bool ok = act && tok < p.N;
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
       bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-      qf[c] = ok ? *reinterpret_cast<const bf16x8*>(qbase + tok * D + 16 * c + 8 * hh) : z;
+      qf[c] = ok ? *reinterpret_cast<const bf16x8*>(qrow + 16 * c + 8 * hh) : z;
     }
-  }
+  };
 
-  // ---- the tile sequence ----
-  __shared__ int s_tile[TILE_CAP];     // first key of tile t (explicit lists only)
-  __shared__ int s_cnt[2];             // tiles in total, tiles before the diagonal block
-  int n_tiles, n_before;
-  if (p.dense) {
-    n_before = i * p.subs;                 // blocks 0..i-1 in full, then the needed part of block i
-    n_tiles = n_before + subs_diag;
-  } else {
+  // ---- start of the stream: tables of the first two items, fills 0..NS-2, Q of the first item ----
+  it = digits((uint32_t)((int64_t)xcd * p.per_xcd + cuslot));
+  finish_item(it);
+  it1 = next_item(it);
+  it2 = next_item(it1);
+  if (!p.dense) {
     if (wave == 0) {
-      // the first wavefront reads the row of the list, 64 entries at a time, and writes the tiles of the
-      // blocks before the diagonal one in list order (ranks by a prefix count over the lanes)
-      int n = p.kv_cnt[i];
-      if (n > p.max_k) n = p.max_k;
-      n = __builtin_amdgcn_readfirstlane(n);
-      int blocks = 0;
-      bool has_diag = false;
-      for (int base = 0; base < n; base += 64) {
-        const int e = base + lane;
-        const int j = e < n ? p.kv_idx[(int64_t)i * p.max_k + e] : -1;
-        const bool valid = j >= 0 && j < i;                  // not padding, causal, not the diagonal block (below)
-        const uint64_t vm = __builtin_amdgcn_ballot_w64(valid);
-        has_diag = has_diag || __builtin_amdgcn_ballot_w64(j == i) != 0;
-        const int rank = blocks + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(vm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)vm, 0));
-        if (valid)
-          for (int u = 0; u < p.subs; ++u) s_tile[rank * p.subs + u] = j * p.B + u * KT;
-        blocks += __builtin_popcountll(vm);
-      }
-      int w = blocks * p.subs;
-      if (lane == 0) s_cnt[1] = w;
-      if (has_diag) {
-        if (lane < subs_diag) s_tile[w + lane] = i * p.B + lane * KT;
-        w += subs_diag;
-      }
-      if (lane == 0) s_cnt[0] = w;
+      table_from_memory(0, it);
+      if (chained) table_from_memory(1, it1);
     }
     __syncthreads();
-    n_tiles = s_cnt[0];
-    n_before = s_cnt[1];
   }
-  n_tiles = __builtin_amdgcn_readfirstlane(n_tiles);
-  n_before = __builtin_amdgcn_readfirstlane(n_before);
-  auto tile_key0 = [&](int t) -> int {       // wavefront-uniform
-    return p.dense ? t * KT : __builtin_amdgcn_readfirstlane(s_tile[t]);
-  };
-  // tiles this wavefront computes: everything before the diagonal block, then the diagonal tiles
-  // that start at or before its last query (later ones are fully masked for it)
-  int n_my = 0;
-  if (active) {
-    int dg = n_tiles - n_before;
-    const int need = (q_in_blk + QW - 1) / KT + 1;
-    if (dg > need) dg = need;
-    n_my = n_before + dg;
-  }
-  n_my = __builtin_amdgcn_readfirstlane(n_my);
+  cursor_enter(0, it);
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s) { next_fill(); fill_all(); }
+  load_q(it);
 
-  // ---- fill the ring: the copies run NS-1 tiles ahead ----
-#pragma unroll
-  for (int s = 0; s < NS - 1; ++s)
-    if (s < n_tiles) issue_tile(tile_key0(s), s);
-
-  f32x16 O[ND];
-#pragma unroll
-  for (int dt = 0; dt < ND; ++dt)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) O[dt][r] = 0.f;
-
-  // Per-lane byte offsets of the swizzled LDS reads inside a stage, computed once: the XOR cannot
-  // be folded into an instruction's immediate offset, the row steps (32 rows of K, 16 and 8 rows of V)
-  // can.
-  uint32_t k_off[NC];                 // K fragment of d-step c, row ln
-  {
-    const int sw = swz<D>(ln);        // rows 32rt + ln share their low bits with ln
-#pragma unroll
-    for (int c = 0; c < NC; ++c) k_off[c] = ln * ROWB + (((2 * c + hh) ^ sw) << 4);
-  }
-  uint32_t v_off0[ND], v_off1[ND];    // the two transposing reads of d tile dt, 16-key step 0
+  // Per-lane LDS base addresses of the fragment reads: ka inside the stage whose K tile is multiplied next,
+  // va inside the stage whose V tile is multiplied next; they are advanced in place from stage to stage.
+  // K fragment (d-step c, key half rt) of lane (ln, hh): row 32rt + ln, chunk 2c + hh.
+  constexpr int K_C = 32 * RPI, K_RT = (32 / RPI) * SRB;                 // offsets per d-step and per key half
+  uint32_t ka = lds0 + (ln / RPI) * SRB + ((hh * RPI + ln % RPI) << 4);
+  // V^T fragment (16-key step kk, d tile dt): two transposing reads, rows 16kk + r4 and 16kk + r4 + 8,
+  // chunk 4dt + x, 8-byte half lane&1
+  constexpr int V_KK = (16 / RPI) * SRB, V_DT = 4 * RPI * 16, V_HI = (8 / RPI) * SRB;
+  uint32_t va;
   {
     const int r4 = 4 * hh + ((lane & 15) >> 2);              // row of the first read inside a 16-key step
     const int x = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1); // chunk inside the 32-wide d tile
-#pragma unroll
-    for (int dt = 0; dt < ND; ++dt) {
-      v_off0[dt] = TILEB + r4 * ROWB + (((4 * dt + x) ^ swz<D>(r4)) << 4) + 8 * (lane & 1);
-      v_off1[dt] = TILEB + (r4 + 8) * ROWB + (((4 * dt + x) ^ swz<D>(r4 + 8)) << 4) + 8 * (lane & 1);
-    }
+    va = lds0 + TILEB + (r4 / RPI) * SRB + ((x * RPI + r4 % RPI) << 4) + 8 * (lane & 1);
   }
+  int k_stage = 0, v_stage = 0;       // ring stages ka and va point into
+  auto advance = [&](uint32_t& addr, int& stage) {
+    addr += stage == NS - 1 ? (uint32_t)(-(NS - 1) * STAGEB) : (uint32_t)STAGEB;
+    stage = stage == NS - 1 ? 0 : stage + 1;
+  };
 
   // ---- pieces of the pipeline ----
   constexpr int NSLOT = 2 * NC + 4 * ND;   // matrix instructions per tile: 32 at head_dim 128, 16 at 64
   constexpr int VPS = 32 / NSLOT;          // the vector work of a tile is cut into 32 portions: portions per matrix instruction
-  constexpr int PF = 3;                    // LDS reads run this many matrix instructions ahead of their use
+  constexpr int PF = 2;                    // LDS reads are issued for a pair of matrix instructions at a time, one pair ahead
   const f32x16 zero16 = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  int q_in_blk = 0;                        // first query of this wavefront inside the block (per item)
 
   // causal mask inside the diagonal block; element rg (0..31) of a tile is key 32(rg/16) + 8((rg%16)/4) + 4hh + rg%4
   auto mask = [&](f32x16 (&S)[2], int key_in_blk) {
@@ -312,203 +394,261 @@ void pa_prefill_bf16_kernel(bf16_params p) {
   };
   // A operand of matrix instruction `slot` of a tile step: K rows (slots 0..2NC-1: d-step c = slot/2, key half
   // rt = slot%2), then V^T (16-key step kk, d tile dt) through two transposing reads
-  auto load_frag = [&](int slot, const uint32_t (&ka)[NC], const uint32_t (&va0)[ND], const uint32_t (&va1)[ND]) -> bf16x8 {
+  auto load_frag = [&](int slot) -> bf16x8 {
     if (slot < 2 * NC)
-      return *reinterpret_cast<const lds_bf16x8*>((uintptr_t)(ka[slot >> 1] + (slot & 1) * (32 * ROWB)));
+      return *reinterpret_cast<const lds_bf16x8*>((uintptr_t)(ka + (slot >> 1) * K_C + (slot & 1) * K_RT));
     const int kk = (slot - 2 * NC) / ND, dt = (slot - 2 * NC) % ND;
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(va0[dt] + kk * (16 * ROWB)));
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(va1[dt] + kk * (16 * ROWB)));
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(va + kk * V_KK + dt * V_DT));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(va + kk * V_KK + dt * V_DT + V_HI));
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
   };
-  auto stage_addresses = [&](int kstage, int vstage, uint32_t (&ka)[NC], uint32_t (&va0)[ND], uint32_t (&va1)[ND]) {
-#pragma unroll
-    for (int c = 0; c < NC; ++c) ka[c] = lds0 + kstage * STAGEB + k_off[c];
-#pragma unroll
-    for (int dt = 0; dt < ND; ++dt) {
-      va0[dt] = lds0 + vstage * STAGEB + v_off0[dt];
-      va1[dt] = lds0 + vstage * STAGEB + v_off1[dt];
-    }
-  };
 
-  // Q fragments and the first tiles must have arrived before the loop; waiting here, once, also tells
-  // the compiler that none of its own loads is outstanding inside the loop, so that it does not add
+  // Q fragments and the first tiles must have arrived before the first item; waiting here, once, also tells
+  // the compiler that none of its own loads is outstanding inside the loops, so that it does not add
   // full vmcnt(0) waits there (they would drain the asynchronous copies as well).
   wait_vmcnt<0>();
   __syncthreads();
 
-  // ---- pipeline state: scores of the current tile, the probabilities of its first 16-key step, running (m, l) ----
-  // The reference point m of the exponentials need not be the exact running maximum: any m gives the
-  // same o and lse as long as exp2(s - m) stays in range.  It is raised only when a score exceeds it by
-  // more than RESCALE_TAU (p <= 2^tau), which makes the rescaling of O (64 multiplies per lane) a
-  // rare, wavefront-uniform branch instead of a per-tile cost.
-  f32x16 Sc[2];
-  u32x4 P0;
-  float m_run = -INFINITY, l_run = 0.f;
-  if (n_my > 0) {
-    uint32_t ka[NC], va0[ND], va1[ND];
-    stage_addresses(0, 0, ka, va0, va1);
-#pragma unroll
-    for (int sl2 = 0; sl2 < 2 * NC; ++sl2)
-      Sc[sl2 & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(load_frag(sl2, ka, va0, va1), qf[sl2 >> 1],
-                                                            sl2 < 2 ? zero16 : Sc[sl2 & 1], 0, 0, 0);
-    if (n_before == 0) mask(Sc, 0);        // the first tile is already a diagonal one
-    float mx = Sc[0][0];
-#pragma unroll
-    for (int rg = 1; rg < 32; ++rg) mx = fmaxf(mx, Sc[rg >> 4][rg & 15]);
-    m_run = both_halves_max(mx) * p.c2;
-    float pe[8];
-#pragma unroll
-    for (int rg = 0; rg < 8; ++rg) { pe[rg] = pexp(Sc, rg, m_run); l_run += pe[rg]; }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) P0[j] = pack2(pe[2 * j], pe[2 * j + 1]);
-  }
+  for (int k = 0; k < n_items; ++k) {
+    const bool more = k + 1 < n_items;
+    // ---- per-item geometry ----
+    const int task = it.chunk * NW + wave;
+    const bool active = task < p.tasks;
+    const int g = active ? task / slices : 0;
+    const int sl = active ? task % slices : 0;
+    const int h = it.kvh * p.G + g;
+    q_in_blk = sl * QW;
+    const int64_t q0 = (int64_t)it.i * p.B + q_in_blk;
+    int n_tiles, n_before;
+    if (p.dense) {
+      n_before = it.i * p.subs;               // blocks 0..i-1 in full, then the needed part of block i
+      n_tiles = n_before + it.subs_diag;
+    } else {
+      n_tiles = __builtin_amdgcn_readfirstlane(s_cnt[k & 1][0]);
+      n_before = __builtin_amdgcn_readfirstlane(s_cnt[k & 1][1]);
+    }
+    const int n_steps = (more && n_tiles < MIN_STEPS) ? MIN_STEPS : n_tiles;
+    // tiles this wavefront computes: everything before the diagonal block, then the diagonal tiles
+    // that start at or before its last query (later ones are fully masked for it)
+    int n_my = 0;
+    if (active) {
+      int dg = n_tiles - n_before;
+      const int need = (q_in_blk + QW - 1) / KT + 1;
+      if (dg > need) dg = need;
+      n_my = n_before + dg;
+    }
+    n_my = __builtin_amdgcn_readfirstlane(n_my);
 
-  // Start of every iteration: tile t+1 has landed once at most tile t+2's copies are outstanding
-  // (tiles 0..NS-2 landed above); the barrier makes every wavefront's share of it visible and tells
-  // that everybody is done with tile t-1, whose stage is refilled.
-  auto top = [&](int t) {
-    if (t + 2 < n_tiles) wait_vmcnt<LPT>(); else wait_vmcnt<0>();
-    __syncthreads();
-    if (t + NS - 1 < n_tiles) issue_tile(tile_key0(t + NS - 1), (t + NS - 1) % NS);
-  };
+    // The Q rows requested during the previous item are needed from here on.  Touching them on every path
+    // makes the compiler wait for them here, once, instead of guarding each later use inside the loops
+    // with a wait that would also drain the asynchronous copies.
+#pragma unroll
+    for (int c = 0; c < NC; ++c) asm volatile("" : "+v"(qf[c]));
 
-  // One step of the skewed loop.  Matrix instructions: the 2NC of S(t+1) = K(t+1) Q^T, then the 4ND of
-  // O += V(t)^T P(t)^T.  Vector work, cut into 32 portions that are spread evenly over them: the
-  // exponentials of elements 8..31 of S(t) (element rg feeds 16-key step rg/8 of the second product, so
-  // each is ready before its step), then the column maximum of S(t+1) and the new reference point, then the
-  // exponentials of elements 0..7 of S(t+1).  The source order IS the schedule: a scheduling barrier after
-  // every matrix instruction keeps the compiler from regrouping the stream into a matrix phase and a
-  // vector phase.  `masked` selects the variant that applies the causal mask to S(t+1).
-  auto step = [&](int t, auto masked) {
-    constexpr bool MASKED = decltype(masked)::value;
-    uint32_t ka[NC], va0[ND], va1[ND];
-    stage_addresses((t + 1) % NS, t % NS, ka, va0, va1);
-    top(t);
-    bf16x8 fr[NSLOT];
-    f32x16 Sn[2];
-    u32x4 Pk[4], Pn;
-    Pk[0] = P0;
-    float pe[32], pn[8];
-    float rs = 0.f, rs_n = 0.f, mx = 0.f, m_new = 0.f, alpha = 1.f;
-    bool raise = false;
+    // ---- look-ahead: the table of the next item from its prefetched list row (the first two tables were
+    // built above), and the copy of the row of the item after it ----
+    if (chained) {
+      if (!p.dense && wave == 0 && k >= 1 && more) table_from_row((k + 1) & 1, it1);
+      copy_row(k + 2 < n_items ? it2 : it);
+    }
+
+    f32x16 O[ND];
 #pragma unroll
-    for (int s0 = 0; s0 < PF; ++s0) fr[s0] = load_frag(s0, ka, va0, va1);
+    for (int dt = 0; dt < ND; ++dt)
 #pragma unroll
-    for (int sl2 = 0; sl2 < NSLOT; ++sl2) {
-      if (sl2 + PF < NSLOT) fr[sl2 + PF] = load_frag(sl2 + PF, ka, va0, va1);
-      // ---- vector portions of this slot ----
+      for (int r = 0; r < 16; ++r) O[dt][r] = 0.f;
+
+    // ---- pipeline state: scores of the current tile, the probabilities of its first 16-key step, running (m, l) ----
+    // The reference point m of the exponentials need not be the exact running maximum: any m gives the
+    // same o and lse as long as exp2(s - m) stays in range.  It is raised only when a score exceeds it by
+    // more than RESCALE_TAU (p <= 2^tau), which makes the rescaling of O (64 multiplies per lane) a
+    // rare, wavefront-uniform branch instead of a per-tile cost.
+    f32x16 Sc[2];
+    u32x4 P0;
+    float m_run = -INFINITY, l_run = 0.f;
+    if (n_my > 0) {
 #pragma unroll
-      for (int vs = sl2 * VPS; vs < (sl2 + 1) * VPS; ++vs) {
-        if (vs < 18) {
+      for (int sl2 = 0; sl2 < 2 * NC; ++sl2)
+        Sc[sl2 & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(load_frag(sl2), qf[sl2 >> 1],
+                                                              sl2 < 2 ? zero16 : Sc[sl2 & 1], 0, 0, 0);
+      if (n_before == 0) mask(Sc, 0);        // the first tile is already a diagonal one
+      float mx = Sc[0][0];
 #pragma unroll
-          for (int e = (4 * vs) / 3; e < (4 * (vs + 1)) / 3; ++e) {
-            const int rg = 8 + e;
-            pe[rg] = pexp(Sc, rg, m_run);
-            rs += pe[rg];
-            if (rg & 1) Pk[rg >> 3][(rg & 7) >> 1] = pack2(pe[rg - 1], pe[rg]);
+      for (int rg = 1; rg < 32; ++rg) mx = fmaxf(mx, Sc[rg >> 4][rg & 15]);
+      m_run = both_halves_max(mx) * p.c2;
+      float pe[8];
+#pragma unroll
+      for (int rg = 0; rg < 8; ++rg) { pe[rg] = pexp(Sc, rg, m_run); l_run += pe[rg]; }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) P0[j] = pack2(pe[2 * j], pe[2 * j + 1]);
+    }
+
+    // Start of every step: the fill after this step's (it carries K of the next tile) has landed once at most
+    // the one younger fill's copies are outstanding, plus, in the first two steps of an item, the list-row copy
+    // issued at its start.  The barrier makes every wavefront's share visible and tells that everybody is done
+    // with the stage of the previous step, which the fill prepared here overwrites.
+    auto top = [&](int t) {
+      if (chained && t < 2) wait_vmcnt<LPT + 1>(); else wait_vmcnt<LPT>();
+      __syncthreads();
+      next_fill();
+    };
+
+    // One step of the skewed loop.  Matrix instructions: the 2NC of S(t+1) = K(t+1) Q^T, then the 4ND of
+    // O += V(t)^T P(t)^T.  Vector work, cut into 32 portions that are spread evenly over them: the
+    // exponentials of elements 8..31 of S(t) (element rg feeds 16-key step rg/8 of the second product, so
+    // each is ready before its step), then the column maximum of S(t+1) and the new reference point, then the
+    // exponentials of elements 0..7 of S(t+1).  The source order IS the schedule: a scheduling barrier after
+    // every matrix instruction keeps the compiler from regrouping the stream into a matrix phase and a
+    // vector phase.  `masked` selects the variant that applies the causal mask to S(t+1).
+    auto step = [&](int t, auto masked) {
+      constexpr bool MASKED = decltype(masked)::value;
+      advance(ka, k_stage);               // K(t+1) sits one stage after V(t)
+      top(t);
+      bf16x8 fr[NSLOT];
+      f32x16 Sn[2];
+      u32x4 Pk[4], Pn;
+      Pk[0] = P0;
+      float pe[32], pn[8];
+      float rs = 0.f, rs_n = 0.f, mx = 0.f, m_new = 0.f, alpha = 1.f;
+      bool raise = false;
+#pragma unroll
+      for (int s0 = 0; s0 < PF; ++s0) fr[s0] = load_frag(s0);
+#pragma unroll
+      for (int sl2 = 0; sl2 < NSLOT; ++sl2) {
+        if (sl2 % 2 == 0 && sl2 + PF < NSLOT) { fr[sl2 + PF] = load_frag(sl2 + PF); fr[sl2 + PF + 1] = load_frag(sl2 + PF + 1); }
+        // ---- one of the LPT copies of the fill, evenly spread ----
+        if ((sl2 % (NSLOT / LPT)) == NSLOT / LPT / 2) fill_part(sl2 / (NSLOT / LPT));
+        // ---- vector portions of this slot ----
+#pragma unroll
+        for (int vs = sl2 * VPS; vs < (sl2 + 1) * VPS; ++vs) {
+          if (vs < 18) {
+#pragma unroll
+            for (int e = (4 * vs) / 3; e < (4 * (vs + 1)) / 3; ++e) {
+              const int rg = 8 + e;
+              pe[rg] = pexp(Sc, rg, m_run);
+              rs += pe[rg];
+              if (rg & 1) Pk[rg >> 3][(rg & 7) >> 1] = pack2(pe[rg - 1], pe[rg]);
+            }
+            if (MASKED && vs == 17) mask(Sn, (t + 1 - n_before) * KT);
+          } else if (vs < 21) {
+            constexpr int lo[3] = {0, 11, 22}, hi[3] = {11, 22, 32};
+            if (vs == 18) mx = Sn[0][0];
+#pragma unroll
+            for (int rg = lo[vs - 18]; rg < hi[vs - 18]; ++rg) mx = fmaxf(mx, Sn[rg >> 4][rg & 15]);
+          } else if (vs == 21) {
+            mx = both_halves_max(mx) * p.c2;
+            raise = mx > m_run + RESCALE_TAU;
+          } else if (vs == 22) {
+            m_new = raise ? mx : m_run;
+            alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+          } else if (vs < 29) {
+#pragma unroll
+            for (int rg = (4 * (vs - 23)) / 3; rg < (4 * (vs - 22)) / 3; ++rg) {
+              pn[rg] = pexp(Sn, rg, m_new);
+              rs_n += pn[rg];
+              if (rg & 1) Pn[rg >> 1] = pack2(pn[rg - 1], pn[rg]);
+            }
+            // results that are only used by the next step: keep their computation here, in the shadow of
+            // the matrix instructions, instead of letting it sink to the end of the iteration
+            if (vs == 28) asm volatile("" ::"v"(Pn), "v"(rs_n));
           }
-          if (MASKED && vs == 17) mask(Sn, (t + 1 - n_before) * KT);
-        } else if (vs < 21) {
-          constexpr int lo[3] = {0, 11, 22}, hi[3] = {11, 22, 32};
-          if (vs == 18) mx = Sn[0][0];
-#pragma unroll
-          for (int rg = lo[vs - 18]; rg < hi[vs - 18]; ++rg) mx = fmaxf(mx, Sn[rg >> 4][rg & 15]);
-        } else if (vs == 21) {
-          mx = both_halves_max(mx) * p.c2;
-          raise = mx > m_run + RESCALE_TAU;
-        } else if (vs == 22) {
-          m_new = raise ? mx : m_run;
-          alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        } else if (vs < 29) {
-#pragma unroll
-          for (int rg = (4 * (vs - 23)) / 3; rg < (4 * (vs - 22)) / 3; ++rg) {
-            pn[rg] = pexp(Sn, rg, m_new);
-            rs_n += pn[rg];
-            if (rg & 1) Pn[rg >> 1] = pack2(pn[rg - 1], pn[rg]);
-          }
-          // results that are only used by the next step: keep their computation here, in the shadow of
-          // the matrix instructions, instead of letting it sink to the end of the iteration
-          if (vs == 28) asm volatile("" ::"v"(Pn), "v"(rs_n));
         }
+        // ---- the matrix instruction: within a pair the second one goes first, because it waits for the pair's
+        // last read and so covers the other one's as well (one wait per pair instead of two) ----
+        {
+          const int ms = sl2 ^ 1;
+          if (ms < 2 * NC) {
+            Sn[ms & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[ms], qf[ms >> 1], ms < 2 ? zero16 : Sn[ms & 1], 0, 0, 0);
+          } else {
+            const int kk = (ms - 2 * NC) / ND, dt = (ms - 2 * NC) % ND;
+            O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[ms], __builtin_bit_cast(bf16x8, Pk[kk]), O[dt], 0, 0, 0);
+          }
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
-      // ---- the matrix instruction ----
-      if (sl2 < 2 * NC) {
-        Sn[sl2 & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[sl2], qf[sl2 >> 1], sl2 < 2 ? zero16 : Sn[sl2 & 1], 0, 0, 0);
-      } else {
+      l_run += rs;
+      if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+        l_run *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < ND; ++dt)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
+      }
+      l_run += rs_n;
+      m_run = m_new;
+      Sc[0] = Sn[0]; Sc[1] = Sn[1];
+      P0 = Pn;
+      advance(va, v_stage);
+    };
+    // Only the last tile a wavefront computes needs the mask: the diagonal tiles before it lie entirely
+    // below its first query.  Every wavefront runs n_steps iterations (the barriers are shared): plain
+    // steps, masked steps, its last tile, then idle iterations that only copy.  In the last iteration of the
+    // item the Q rows of the next item are requested: no product with Q is left by then.
+    int t_mask = n_before + q_in_blk / KT;
+    if (t_mask > n_my) t_mask = n_my;
+    const int T1 = t_mask > 1 ? t_mask - 1 : 0, T2 = n_my > 1 ? n_my - 1 : 0;
+    int t = 0;
+    for (; t < T1; ++t) step(t, std::false_type{});
+    for (; t < T2; ++t) step(t, std::true_type{});
+    for (; t < n_my; ++t) {
+      // ---- last tile of this wavefront: the rest of P(t), O += P(t) V(t) ----
+      advance(ka, k_stage);
+      top(t);
+      fill_all();
+      if (more && t == n_steps - 1) load_q(it1);
+      u32x4 Pk[4];
+      Pk[0] = P0;
+      float pe[32];
+#pragma unroll
+      for (int rg = 8; rg < 32; ++rg) {
+        pe[rg] = pexp(Sc, rg, m_run);
+        l_run += pe[rg];
+        if (rg & 1) Pk[rg >> 3][(rg & 7) >> 1] = pack2(pe[rg - 1], pe[rg]);
+      }
+#pragma unroll
+      for (int sl2 = 2 * NC; sl2 < NSLOT; ++sl2) {
         const int kk = (sl2 - 2 * NC) / ND, dt = (sl2 - 2 * NC) % ND;
-        O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[sl2], __builtin_bit_cast(bf16x8, Pk[kk]), O[dt], 0, 0, 0);
+        O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(load_frag(sl2), __builtin_bit_cast(bf16x8, Pk[kk]), O[dt], 0, 0, 0);
       }
-      __builtin_amdgcn_sched_barrier(0);
+      advance(va, v_stage);
     }
-    l_run += rs;
-    if (__builtin_amdgcn_ballot_w64(raise) != 0) {
-      l_run *= alpha;
-#pragma unroll
-      for (int dt = 0; dt < ND; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) O[dt][r] *= alpha;
+    for (; t < n_steps; ++t) {
+      advance(ka, k_stage);
+      top(t);
+      fill_all();
+      if (more && t == n_steps - 1) load_q(it1);
+      advance(va, v_stage);
     }
-    l_run += rs_n;
-    m_run = m_new;
-    Sc[0] = Sn[0]; Sc[1] = Sn[1];
-    P0 = Pn;
-  };
-  // Only the last tile a wavefront computes needs the mask: the diagonal tiles before it lie entirely
-  // below its first query.  Every wavefront runs n_tiles iterations (the barriers are shared): plain
-  // steps, masked steps, its last tile, then idle iterations that only copy.
-  int t_mask = n_before + q_in_blk / KT;
-  if (t_mask > n_my) t_mask = n_my;
-  const int T1 = t_mask > 1 ? t_mask - 1 : 0, T2 = n_my > 1 ? n_my - 1 : 0;
-  int t = 0;
-  for (; t < T1; ++t) step(t, std::false_type{});
-  for (; t < T2; ++t) step(t, std::true_type{});
-  for (; t < n_my; ++t) {
-    // ---- last tile of this wavefront: the rest of P(t), O += P(t) V(t) ----
-    uint32_t ka[NC], va0[ND], va1[ND];
-    stage_addresses(t % NS, t % NS, ka, va0, va1);
-    top(t);
-    u32x4 Pk[4];
-    Pk[0] = P0;
-    float pe[32];
-#pragma unroll
-    for (int rg = 8; rg < 32; ++rg) {
-      pe[rg] = pexp(Sc, rg, m_run);
-      l_run += pe[rg];
-      if (rg & 1) Pk[rg >> 3][(rg & 7) >> 1] = pack2(pe[rg - 1], pe[rg]);
-    }
-#pragma unroll
-    for (int sl2 = 2 * NC; sl2 < NSLOT; ++sl2) {
-      const int kk = (sl2 - 2 * NC) / ND, dt = (sl2 - 2 * NC) % ND;
-      O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(load_frag(sl2, ka, va0, va1), __builtin_bit_cast(bf16x8, Pk[kk]), O[dt], 0, 0, 0);
-    }
-  }
-  for (; t < n_tiles; ++t) top(t);
 
-  // ---- epilogue: register r of tile dt is d = 32dt + 8(r/4) + 4hh + r%4 ----
-  {
-    const float ltot = l_run + __shfl_xor(l_run, 32);
-    const float inv = ltot > 0.f ? 1.0f / ltot : 0.f;
-    const int64_t tok = q0 + ln;
-    if (active && tok < p.N) {
-      __bf16* orow = p.o + (((int64_t)b * p.hq + h) * p.N + tok) * D;
+    // ---- epilogue: register r of tile dt is d = 32dt + 8(r/4) + 4hh + r%4 ----
+    {
+      const float ltot = l_run + __shfl_xor(l_run, 32);
+      const float inv = ltot > 0.f ? 1.0f / ltot : 0.f;
+      const int64_t tok = q0 + ln;
+      if (active && tok < p.N) {
+        __bf16* orow = p.o + (((int64_t)it.b * p.hq + h) * p.N + tok) * D;
 #pragma unroll
-      for (int dt = 0; dt < ND; ++dt)
+        for (int dt = 0; dt < ND; ++dt)
 #pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
-          bf16x4 w;
+          for (int g4 = 0; g4 < 4; ++g4) {
+            bf16x4 w;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) w[e] = (__bf16)(O[dt][4 * g4 + e] * inv);
-          *reinterpret_cast<bf16x4*>(orow + 32 * dt + 8 * g4 + 4 * hh) = w;
-        }
-      if (p.lse && hh == 0)
-        p.lse[((int64_t)b * p.hq + h) * p.N + tok] = (m_run + log2f(ltot)) * 0.69314718055994530942f;
+            for (int e = 0; e < 4; ++e) w[e] = (__bf16)(O[dt][4 * g4 + e] * inv);
+            *reinterpret_cast<bf16x4*>(orow + 32 * dt + 8 * g4 + 4 * hh) = w;
+          }
+        if (p.lse && hh == 0)
+          p.lse[((int64_t)it.b * p.hq + h) * p.N + tok] = (m_run + log2f(ltot)) * 0.69314718055994530942f;
+      }
     }
+    it = it1; it1 = it2; it2 = next_item(it2);
   }
+  // asynchronous copies must not outlive the workgroup's claim on its LDS
+  wait_vmcnt<0>();
 }
 
 template <int D, int NW, int NS>
 int launch(const bf16_params& p, hipStream_t stream) {
-  constexpr size_t lds = (size_t)NS * 2 * KT * 2 * D;
+  constexpr size_t lds = (size_t)NS * 2 * (KT / (512 / D)) * (1024 + 16 * (512 / D));
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pa_prefill_bf16_kernel<D, NW, NS>),
@@ -516,7 +656,21 @@ int launch(const bf16_params& p, hipStream_t stream) {
     if (e != hipSuccess) return pa_note_hip(e);
     attr_done = true;
   }
-  const int64_t grid = (int64_t)p.per_xcd * 8;
+  // One workgroup per work item, or, when the items can be chained (the block lists are short enough for the
+  // look-ahead tables and registers), one persistent workgroup per compute unit that walks through its share.
+  int64_t grid = (int64_t)p.per_xcd * 8;
+  if (p.chain) {
+    static int n_cu[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+    if (n_cu[dev] == 0) {
+      int v = 0;
+      if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 8) v = 8;
+      n_cu[dev] = v;
+    }
+    const int64_t persistent = (int64_t)(n_cu[dev] / 8) * 8;
+    if (grid > persistent) grid = persistent;
+  }
   hipLaunchKernelGGL((pa_prefill_bf16_kernel<D, NW, NS>), dim3((uint32_t)grid), dim3(64 * NW), lds, stream, p);
   return pa_note_hip(hipGetLastError());
 }
@@ -542,6 +696,8 @@ int pa_launch_prefill_bf16(const pa_prefill_args& a) {
   const int64_t per_xcd = (p.total_wg + 7) / 8;
   if (per_xcd * 8 > 0x7fffffffLL) return POWATTN_UNSUPPORTED;
   p.per_xcd = (int32_t)per_xcd;
+  // chaining keeps the list row of the item after next in 63 lanes and two tile tables in LDS
+  p.chain = (p.dense || (a.max_k <= 63 && (int64_t)a.max_k * p.subs <= TILE_CAP / 2)) ? 1 : 0;
 
   // ring of 4 stages: 128 KB of LDS at head_dim 128, 64 KB at head_dim 64
   if (a.head_dim == 128) return nw == 8 ? launch<128, 8, 4>(p, a.stream) : launch<128, 4, 4>(p, a.stream);
