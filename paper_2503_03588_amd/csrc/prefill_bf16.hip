@@ -620,25 +620,72 @@ void pa_prefill_bf16_kernel(bf16_params p) {
       advance(va, v_stage);
     }
 
-    // ---- epilogue: register r of tile dt is d = 32dt + 8(r/4) + 4hh + r%4 ----
+    // ---- epilogue ----
+    // Register r of tile dt is d = 32dt + 8(r/4) + 4hh + r%4: a lane holds every other 8-byte piece of its
+    // output row and lane+32 the pieces in between.  The two lanes first trade pieces (the upper half of the
+    // wavefront's copy of one register against the lower half's copy of another) so that lane (q, 0) ends up
+    // with the first half of the row and lane (q, 1) with the second, in 16-byte chunks; the row then leaves in
+    // half as many, twice as wide stores, which matters because the stores of a whole workgroup queue up in
+    // the compute unit's one address unit at the end of every work item.
     {
       const float ltot = l_run + __shfl_xor(l_run, 32);
       const float inv = ltot > 0.f ? 1.0f / ltot : 0.f;
       const int64_t tok = q0 + ln;
-      if (active && tok < p.N) {
-        __bf16* orow = p.o + (((int64_t)it.b * p.hq + h) * p.N + tok) * D;
+      constexpr int NP = 4 * ND;                       // 8-byte pieces per lane; piece pc sits at byte 16pc + 8hh of the row
+      uint32_t pw[NP][2];
 #pragma unroll
-        for (int dt = 0; dt < ND; ++dt)
-#pragma unroll
-          for (int g4 = 0; g4 < 4; ++g4) {
-            bf16x4 w;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) w[e] = (__bf16)(O[dt][4 * g4 + e] * inv);
-            *reinterpret_cast<bf16x4*>(orow + 32 * dt + 8 * g4 + 4 * hh) = w;
-          }
-        if (p.lse && hh == 0)
-          p.lse[((int64_t)it.b * p.hq + h) * p.N + tok] = (m_run + log2f(ltot)) * 0.69314718055994530942f;
+      for (int pc = 0; pc < NP; ++pc) {
+        const int dt = pc >> 2, r0 = 4 * (pc & 3);
+        pw[pc][0] = pack2(O[dt][r0] * inv, O[dt][r0 + 1] * inv);
+        pw[pc][1] = pack2(O[dt][r0 + 2] * inv, O[dt][r0 + 3] * inv);
       }
+#pragma unroll
+      for (int m = 0; m < NP / 2; ++m)
+#pragma unroll
+        for (int x = 0; x < 2; ++x) {
+          const auto r = __builtin_amdgcn_permlane32_swap(pw[m][x], pw[m + NP / 2][x], false, false);
+          pw[m][x] = r[0];
+          pw[m + NP / 2][x] = r[1];
+        }
+      // Now lane (q, hh) holds NP/2 chunks of 16 bytes, chunk m at byte D*hh + 16m of row q.  Four consecutive
+      // lanes hold four consecutive rows; a 4x4 transpose inside every such quad (two butterfly stages of
+      // quad permutes) hands lane i chunk 4u+i of all four rows, so that store k of group u writes row k of the
+      // quad with its four lanes covering 64 contiguous bytes instead of four different rows.
+      const bool odd = lane & 1, upper = lane & 2;
+      auto quad_xor1 = [](uint32_t x) -> uint32_t { return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0xB1, 0xF, 0xF, true); };
+      auto quad_xor2 = [](uint32_t x) -> uint32_t { return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0x4E, 0xF, 0xF, true); };
+      const int li = lane & 3;
+      const int64_t tok0 = tok - li;                   // first row of the quad
+      __bf16* obase = p.o + (((int64_t)it.b * p.hq + h) * p.N + tok0) * D + hh * (D / 2) + 8 * li;
+#pragma unroll
+      for (int u = 0; u < NP / 8; ++u) {
+        uint32_t c[4][4];                              // c[m][word]: chunk 4u+m of this lane's row
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+          const int mm = 4 * u + m;
+          c[m][0] = pw[mm][0]; c[m][1] = pw[mm][1]; c[m][2] = pw[mm + NP / 2][0]; c[m][3] = pw[mm + NP / 2][1];
+        }
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          // stage 1: lanes i and i^1 trade c[k^1]; stage 2: lanes i and i^2 trade c[k^2].  The permutes are
+          // evaluated by all lanes before anything is selected: a lane can only be read while it is active.
+          const uint32_t x0 = quad_xor1(c[0][w]), x1 = quad_xor1(c[1][w]), x2 = quad_xor1(c[2][w]), x3 = quad_xor1(c[3][w]);
+          const uint32_t a0 = odd ? x1 : c[0][w], a1 = odd ? c[1][w] : x0;
+          const uint32_t a2 = odd ? x3 : c[2][w], a3 = odd ? c[3][w] : x2;
+          const uint32_t y0 = quad_xor2(a0), y1 = quad_xor2(a1), y2 = quad_xor2(a2), y3 = quad_xor2(a3);
+          c[0][w] = upper ? y2 : a0; c[2][w] = upper ? a2 : y0;
+          c[1][w] = upper ? y3 : a1; c[3][w] = upper ? a3 : y1;
+        }
+        // c[k] is now chunk 4u + li of row tok0 + k
+#pragma unroll
+        for (int k2 = 0; k2 < 4; ++k2) {
+          const u32x4 wv = {c[k2][0], c[k2][1], c[k2][2], c[k2][3]};
+          if (active && tok0 + k2 < p.N)
+            *reinterpret_cast<u32x4*>(obase + (int64_t)k2 * D + 32 * u) = wv;
+        }
+      }
+      if (active && tok < p.N && p.lse && hh == 0)
+        p.lse[((int64_t)it.b * p.hq + h) * p.N + tok] = (m_run + log2f(ltot)) * 0.69314718055994530942f;
     }
     it = it1; it1 = it2; it2 = next_item(it2);
   }
