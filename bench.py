@@ -166,6 +166,38 @@ def main():
                  "block_pair_ratio": round((nb * (nb + 1) / 2) / pairs, 2)}
         del o2
 
+    # ---------------- the paper's own setting (Section 4.1: 256-token blocks, 5-block window, sink) over the
+    # context lengths of its kernel experiment (Section 4.4 / Figure 3b: 16K-128K): sparse and dense kernel
+    # times and their ratio, next to the ratio of attended block pairs; outside the timed region -------------
+    sweep = None
+    if not args.no_dense:
+        sweep = []
+        pat_s = pa.Pattern(256, 5, 1)
+        pat_sd = pa.Pattern(256, 5, 1, flags=pa.DENSE)
+        for n_ctx in (16384, 32768, 65536, 131072):
+            qs, ks_, vs_ = qg[:, :, :n_ctx].contiguous(), kg[:, :, :n_ctx].contiguous(), vg[:, :, :n_ctx].contiguous()
+            os_ = torch.empty_like(qs)
+            c_s, i_s, _ = pa.mask_build(pat_s, n_ctx)
+
+            def timed(fn, iters):
+                fn()
+                torch.cuda.synchronize()
+                a, b = ev(), ev()
+                a.record()
+                for _ in range(iters):
+                    fn()
+                b.record()
+                torch.cuda.synchronize()
+                return a.elapsed_time(b) / iters
+            ms_s = timed(lambda: pa.prefill(pat_s, c_s, i_s, qs, ks_, vs_, o=os_, want_lse=False), 5)
+            ms_d = timed(lambda: pa.prefill(pat_sd, None, None, qs, ks_, vs_, o=os_, want_lse=False),
+                         3 if n_ctx < 131072 else 1)
+            nbs = n_ctx // 256
+            sweep.append({"n": n_ctx, "sparse_ms": round(ms_s, 4), "dense_ms": round(ms_d, 3),
+                          "dense_over_sparse": round(ms_d / ms_s, 2),
+                          "block_pair_ratio": round((nbs * (nbs + 1) / 2) / int(c_s.sum().item()), 2)})
+            del qs, ks_, vs_, os_
+
     # ---------------- CPU oracle on a bounded row sample (also the bench's own parity check) ----------------
     cpu = None
     parity = None
@@ -222,6 +254,7 @@ def main():
                                 "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(decode_gbs / PEAK_HBM_GBS, 4),
                                 "bytes_per_step": decode_bytes, "traffic": None}},
         "dense_baseline": dense,
+        "paper_setting_b256_w5_s1": sweep,
         "parity": parity,
     }
     print(json.dumps(out))

@@ -154,7 +154,10 @@ size_t powattn_decode_workspace_bytes(const powattn_pattern* pattern, int32_t ba
  *   dtype          POWATTN_BF16 only; head_dim 64 or 128; block a multiple of 64
  *   workspace      device, at least powattn_decode_workspace_bytes(...) bytes,
  *                  256-byte aligned; contents on entry are ignored.  Two calls
- *                  that may run at the same time must not share a workspace.
+ *                  that may run at the same time must not share a workspace,
+ *                  and at most 64 calls may be in flight at once per device
+ *                  (the workgroups of a call count themselves in through one
+ *                  of 64 sets of counters in the library's device memory).
  * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR.
  */
 int powattn_decode(const powattn_pattern* pattern,

@@ -20,9 +20,14 @@
 //    accumulator layout of S^T is the B-operand layout of the second product.
 //  * Each wavefront keeps a running (max, sum, O) over its chunks; the eight
 //    partials meet in LDS.  With one workgroup per (sequence, KV head) that is
-//    the result; with several (small batches) the workgroups leave
-//    unnormalised partials in the workspace and a second, tiny kernel merges.
+//    the result; with several, the workgroups leave unnormalised partials in
+//    the workspace and the one that arrives last (an arrival counter per
+//    (sequence, KV head)) merges them: a second launch would cost more than
+//    the whole merge.  Partials, counter and the merging loads act at device
+//    scope by themselves; no fence is used, because a device-scope fence writes
+//    back and invalidates a whole L2 on this chip.
 #include <math.h>
+#include <atomic>
 #include "common.h"
 
 namespace {
@@ -42,8 +47,16 @@ struct dec_params {
   int64_t capacity;
   int32_t B, W, S; uint32_t flags;
   int32_t hq, hkv, G, splits, subs;
+  int32_t fused;        // 1: the last workgroup of a (sequence, KV head) merges the partials itself
+  int32_t region;       // which set of arrival counters this call uses
   float c2;
 };
+
+// Arrival counters of the fused merge: one per (sequence, KV head) and call in flight.  They live in the
+// library's own device memory (zero when the module is loaded, set back to zero by the last arriver), so the
+// caller's workspace needs no initialisation; calls take the sets round-robin.
+constexpr int CTR_SETS = 64, CTR_PER_SET = 4096;
+__device__ unsigned int g_arrivals[CTR_SETS][CTR_PER_SET];
 
 template <int D>
 __global__ __launch_bounds__(64 * NW) void pa_decode_kernel(dec_params p) {
@@ -228,10 +241,50 @@ __global__ __launch_bounds__(64 * NW) void pa_decode_kernel(dec_params p) {
       p.o[((int64_t)b * p.hq + h) * D + d] = (__bf16)(acc / L);      // L > 0: chunk 0 of the row is never empty
       if (p.lse && d == 0) p.lse[(int64_t)b * p.hq + h] = (M + log2f(L)) * 0.69314718055994530942f;
     } else {
+      // Partials go to memory with device scope (written through this XCD's L2): the workgroup that merges
+      // them may sit on another XCD, whose L2 would not see lines that only live in ours.
       float* part = p.partials + (((int64_t)b * p.hq + h) * p.splits + split) * (D + 2);
-      part[d] = acc;
-      if (d == 0) { part[D] = M; part[D + 1] = L; }                  // an idle split leaves M = -inf, L = 0
+      __hip_atomic_store(part + d, acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (d == 0) {                                                  // an idle split leaves M = -inf, L = 0
+        __hip_atomic_store(part + D, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(part + D + 1, L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
     }
+  }
+  if (p.splits == 1 || !p.fused) return;
+
+  // ---- fused merge: the workgroup that arrives last at its (sequence, KV head) combines all partials ----
+  // Every store above has been acknowledged by memory before its thread passes the barrier; then one
+  // thread counts the workgroup in.  No fence is involved: the stores, the counter and the loads below all act
+  // at device scope themselves, and a fence would write back and invalidate this XCD's whole L2.
+  __shared__ unsigned int s_rank;
+  __builtin_amdgcn_s_waitcnt(0);                                     // vmcnt(0), lgkmcnt(0)
+  __syncthreads();
+  unsigned int* ctr = &g_arrivals[p.region][b * p.hkv + kvh];
+  if (tid == 0) s_rank = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
+  if (s_rank != (unsigned)p.splits - 1) return;
+  if (tid == 0) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  for (int e = tid; e < p.G * D; e += 64 * NW) {
+    const int gg = e / D, d = e % D;
+    const int h = kvh * p.G + gg;
+    const float* part = p.partials + ((int64_t)b * p.hq + h) * p.splits * (D + 2);
+    float M = -INFINITY, L = 0.f, acc = 0.f;
+    for (int s0 = 0; s0 < p.splits; ++s0) {
+      const float* ps = part + (int64_t)s0 * (D + 2);
+      const float ms = __hip_atomic_load(ps + D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const float ls = __hip_atomic_load(ps + D + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const float os = __hip_atomic_load(ps + d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (ls > 0.f) {                                                // idle splits hold no outputs
+        const float Mn = fmaxf(M, ms);
+        const float r0 = L > 0.f ? __builtin_amdgcn_exp2f(M - Mn) : 0.f, r1 = __builtin_amdgcn_exp2f(ms - Mn);
+        L = L * r0 + ls * r1;
+        acc = acc * r0 + os * r1;
+        M = Mn;
+      }
+    }
+    p.o[((int64_t)b * p.hq + h) * D + d] = (__bf16)(acc / L);
+    if (p.lse && d == 0) p.lse[(int64_t)b * p.hq + h] = (M + log2f(L)) * 0.69314718055994530942f;
   }
 }
 
@@ -314,6 +367,9 @@ int pa_launch_decode_bf16(const pa_decode_args& a) {
   p.B = a.pat.block; p.W = a.pat.window; p.S = a.pat.sink; p.flags = a.pat.flags;
   p.hq = a.hq; p.hkv = a.hkv; p.G = a.hq / a.hkv; p.splits = a.n_split; p.subs = a.pat.block / CH;
   p.c2 = a.scale * 1.44269504088896340736f;
+  static std::atomic<unsigned> next_region{0};
+  p.fused = (a.n_split > 1 && a.n_split <= 64 && (int64_t)a.batch * a.hkv <= CTR_PER_SET) ? 1 : 0;
+  p.region = p.fused ? (int32_t)(next_region.fetch_add(1) % CTR_SETS) : 0;
   dim3 grid((uint32_t)a.n_split, (uint32_t)a.hkv, (uint32_t)a.batch);
   const size_t lds = (size_t)NW * p.G * a.head_dim * sizeof(float);   // at most 64 KB (G <= 16, D <= 128)
   if (a.head_dim == 128)
@@ -321,7 +377,7 @@ int pa_launch_decode_bf16(const pa_decode_args& a) {
   else
     hipLaunchKernelGGL((pa_decode_kernel<64>), grid, dim3(64 * NW), lds, a.stream, p);
   int st = pa_note_hip(hipGetLastError());
-  if (st != POWATTN_OK || a.n_split == 1) return st;
+  if (st != POWATTN_OK || a.n_split == 1 || p.fused) return st;
   dim3 mgrid((uint32_t)a.hq, (uint32_t)a.batch);
   if (a.head_dim == 128)
     hipLaunchKernelGGL((pa_decode_merge_kernel<128>), mgrid, dim3(64), 0, a.stream, p);
@@ -329,3 +385,4 @@ int pa_launch_decode_bf16(const pa_decode_args& a) {
     hipLaunchKernelGGL((pa_decode_merge_kernel<64>), mgrid, dim3(64), 0, a.stream, p);
   return pa_note_hip(hipGetLastError());
 }
+

@@ -97,3 +97,42 @@ def test_full_size_config4():
                             synth.to_numpy_storage(v[b:b + 1]), [int(lens[b])], orc.Pattern(64, 4, 1))
         assert np.abs(o[b:b + 1].double().cpu().numpy() - oo).max() <= 2e-2
         assert np.abs(lse[b:b + 1].double().cpu().numpy() - ol).max() <= 1e-3
+
+
+def test_many_sequences_take_the_two_kernel_merge():
+    # more (sequence, KV head) pairs than the library keeps arrival counters for: the partials are merged by
+    # the second kernel instead of the last workgroup; sequences are checked at both ends and in the middle
+    pat = pa.Pattern(64, 4, 1)
+    batch, hq, hkv, cap, d = 520, 8, 8, 4096, 128
+    g = torch.Generator(device="cuda"); g.manual_seed(35)
+    k = torch.randn(batch, hkv, cap, d, device="cuda", dtype=torch.bfloat16, generator=g)
+    v = torch.randn(batch, hkv, cap, d, device="cuda", dtype=torch.bfloat16, generator=g)
+    q = torch.randn(batch, hq, d, device="cuda", dtype=torch.bfloat16, generator=g)
+    lens = torch.full((batch,), cap, dtype=torch.int32, device="cuda")
+    lens[7] = cap - 100
+    o, lse = pa.decode(pat, q, k, v, lens)
+    torch.cuda.synchronize()
+    for b in (0, 7, 300, 519):
+        oo, ol = orc.decode(synth.to_numpy_storage(q[b:b + 1]), synth.to_numpy_storage(k[b:b + 1]),
+                            synth.to_numpy_storage(v[b:b + 1]), [int(lens[b])], orc.Pattern(64, 4, 1))
+        assert np.abs(o[b:b + 1].double().cpu().numpy() - oo).max() <= 2e-2
+        assert np.abs(lse[b:b + 1].double().cpu().numpy() - ol).max() <= 1e-3
+
+
+def test_back_to_back_calls_on_one_workspace():
+    # the arrival counters of the fused merge must be back at zero after every call, and a call must not see
+    # partials of the one before: alternate two different inputs many times and compare with fresh results
+    pat = pa.Pattern(64, 4, 1)
+    batch, hq, hkv, cap, d = 4, 8, 2, 8192, 128
+    qa, ka, va = synth.decode_inputs(batch, hq, hkv, cap, d, "bf16", 36)
+    qb, kb, vb = synth.decode_inputs(batch, hq, hkv, cap, d, "bf16", 37)
+    lens = torch.tensor([8192, 8000, 4097, 64], dtype=torch.int32).cuda()
+    A = [t.cuda() for t in (qa, ka, va)]
+    Bt = [t.cuda() for t in (qb, kb, vb)]
+    ws = pa.decode_workspace(pat, batch, hq, hkv, d, cap)
+    ref_a = pa.decode(pat, *A, lens)[0].clone()
+    ref_b = pa.decode(pat, *Bt, lens)[0].clone()
+    torch.cuda.synchronize()
+    for i in range(40):
+        o, _ = pa.decode(pat, *(A if i % 2 == 0 else Bt), lens, workspace=ws)
+        assert torch.equal(o, ref_a if i % 2 == 0 else ref_b), i
