@@ -198,6 +198,50 @@ def main():
                           "block_pair_ratio": round((nbs * (nbs + 1) / 2) / int(c_s.sum().item()), 2)})
             del qs, ks_, vs_, os_
 
+    # ---------------- layer stack (BASELINE configuration 5): 28 successive sparse-attention layers, 28 query /
+    # 4 KV heads, 64K context, block 64, fresh random Q/K/V per layer (no projection weights exist, so the layers
+    # are not chained); per-layer kernel time.  Second pass: the hybrid schedule of Section 4.3, in which 2 of
+    # every 7 layers keep full attention.  Outside the timed region. ----------------
+    stack = None
+    if not args.no_dense:
+        Ls = dict(layers=28, hq=28, hkv=4, n=65536, d=128, B=64, W=4, S=1)
+        pat_l = pa.Pattern(Ls["B"], Ls["W"], Ls["S"])
+        pat_ld = pa.Pattern(Ls["B"], Ls["W"], Ls["S"], flags=pa.DENSE)
+        c_l, i_l, _ = pa.mask_build(pat_l, Ls["n"])
+        gl = torch.Generator(device=dev)
+        layers_in = []
+        for l in range(Ls["layers"]):
+            gl.manual_seed(4000 + l)
+            layers_in.append((torch.randn(1, Ls["hq"], Ls["n"], Ls["d"], device=dev, dtype=torch.bfloat16, generator=gl),
+                              torch.randn(1, Ls["hkv"], Ls["n"], Ls["d"], device=dev, dtype=torch.bfloat16, generator=gl),
+                              torch.randn(1, Ls["hkv"], Ls["n"], Ls["d"], device=dev, dtype=torch.bfloat16, generator=gl)))
+        ol = torch.empty_like(layers_in[0][0])
+
+        def run_stack(dense_layers):
+            a, b = ev(), ev()
+            a.record()
+            for l, (ql, kl, vl) in enumerate(layers_in):
+                if l in dense_layers:
+                    pa.prefill(pat_ld, None, None, ql, kl, vl, o=ol, want_lse=False)
+                else:
+                    pa.prefill(pat_l, c_l, i_l, ql, kl, vl, o=ol, want_lse=False)
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b)
+        run_stack(set())
+        ms_sparse = run_stack(set())
+        hybrid = {l for l in range(Ls["layers"]) if l % 7 in (0, 3)}          # 2 full-attention layers per 7
+        ms_hybrid = run_stack(hybrid)
+        ms_full = run_stack(set(range(Ls["layers"])))
+        pairs_l = int(c_l.sum().item())
+        f_layer = 4.0 * Ls["B"] * Ls["B"] * Ls["d"] * Ls["hq"] * pairs_l
+        stack = {"layers": Ls["layers"], "workload": "28q/4kv heads, N=65536, D=128, block 64, W=4, S=1, bf16",
+                 "sparse_ms_per_layer": round(ms_sparse / Ls["layers"], 4),
+                 "sparse_tflops": round(f_layer * Ls["layers"] / (ms_sparse * 1e-3) / 1e12, 1),
+                 "hybrid_2_dense_per_7_ms_total": round(ms_hybrid, 2), "sparse_ms_total": round(ms_sparse, 2),
+                 "all_dense_ms_total": round(ms_full, 2)}
+        del layers_in, ol
+
     # ---------------- CPU oracle on a bounded row sample (also the bench's own parity check) ----------------
     cpu = None
     parity = None
@@ -255,6 +299,7 @@ def main():
                                 "bytes_per_step": decode_bytes, "traffic": None}},
         "dense_baseline": dense,
         "paper_setting_b256_w5_s1": sweep,
+        "layer_stack": stack,
         "parity": parity,
     }
     print(json.dumps(out))
