@@ -130,6 +130,31 @@ int powattn_prefill(const powattn_pattern* pattern,
                     float softmax_scale, void* hip_stream);
 
 /*
+ * Chunked prefill against a KV cache (what serving needs between powattn_prefill
+ * and powattn_decode: a long prompt processed in pieces, or a prompt appended to
+ * a cached prefix).  The q_len query tokens sit at positions q_start ..
+ * q_start + q_len - 1 of their sequences; the caches already hold the keys and
+ * values of positions 0 .. q_start + q_len - 1.  The result equals rows
+ * q_start .. q_start + q_len - 1 of powattn_prefill over those positions
+ * (Equation 1 with the same A_i), bit for bit.
+ *   d_kv_cnt, d_kv_idx, max_k   block lists indexed by the block number in the
+ *                  whole sequence (as powattn_mask_build writes them for any
+ *                  seq_len >= q_start + q_len, e.g. the cache capacity)
+ *   q, o           device [batch, n_q_heads, q_len, head_dim]
+ *   k_cache, v_cache  device [batch, n_kv_heads, cache_capacity, head_dim]
+ *   lse            device float [batch, n_q_heads, q_len] or NULL
+ *   q_start        a multiple of pattern->block; q_start + q_len <= cache_capacity
+ *   dtype          POWATTN_BF16 only; head_dim 64 or 128; block a multiple of 64
+ * Errors: INVALID_ARG, UNSUPPORTED, HIP_ERROR.
+ */
+int powattn_prefill_chunk(const powattn_pattern* pattern,
+                          const int32_t* d_kv_cnt, const int32_t* d_kv_idx, int32_t max_k,
+                          const void* q, const void* k_cache, const void* v_cache, void* o, float* lse,
+                          int32_t batch, int32_t n_q_heads, int32_t n_kv_heads,
+                          int64_t q_start, int64_t q_len, int64_t cache_capacity,
+                          int32_t head_dim, int32_t dtype, float softmax_scale, void* hip_stream);
+
+/*
  * Bytes of device workspace powattn_decode needs for caches of up to
  * `cache_capacity` tokens (0 on invalid arguments).  It holds the split-K
  * partial results when a (sequence, KV head) is spread over several workgroups.

@@ -23,7 +23,7 @@ BF16, F32 = 0, 1
 EXPORTS = (
     "powattn_version", "powattn_strerror", "powattn_num_blocks", "powattn_max_k",
     "powattn_row_host", "powattn_mask_build", "powattn_prefill",
-    "powattn_decode_workspace_bytes", "powattn_decode",
+    "powattn_prefill_chunk", "powattn_decode_workspace_bytes", "powattn_decode",
 )
 
 
@@ -79,6 +79,8 @@ def lib() -> ctypes.CDLL:
     L.powattn_mask_build.argtypes = [P, i64, vp, vp, i32, vp, vp]
     L.powattn_prefill.restype = ctypes.c_int
     L.powattn_prefill.argtypes = [P, vp, vp, i32, vp, vp, vp, vp, vp, i32, i32, i32, i64, i32, i32, f32, vp]
+    L.powattn_prefill_chunk.restype = ctypes.c_int
+    L.powattn_prefill_chunk.argtypes = [P, vp, vp, i32, vp, vp, vp, vp, vp, i32, i32, i32, i64, i64, i64, i32, i32, f32, vp]
     L.powattn_decode_workspace_bytes.restype = ctypes.c_size_t
     L.powattn_decode_workspace_bytes.argtypes = [P, i32, i32, i32, i32, i64]
     L.powattn_decode.restype = ctypes.c_int
@@ -205,6 +207,31 @@ def prefill(pattern: Pattern, kv_cnt, kv_idx, q, k, v, o=None, lse=None, softmax
                                _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse),
                                batch, hq, hkv, n, d, _dtype_code(q), float(softmax_scale), _stream(stream))
     _check(st, "powattn_prefill")
+    return o, lse
+
+
+def prefill_chunk(pattern: Pattern, kv_cnt, kv_idx, q, k_cache, v_cache, q_start, o=None, lse=None,
+                  softmax_scale=0.0, want_lse=True, stream=None):
+    """powattn_prefill_chunk.  q/o: [b,Hq,q_len,D] at positions q_start..; caches: [b,Hkv,capacity,D] holding
+    positions 0..q_start+q_len-1.  Returns (o, lse)."""
+    batch, hq, q_len, d = q.shape
+    hkv, cap = k_cache.shape[1], k_cache.shape[2]
+    if k_cache.shape != (batch, hkv, cap, d) or v_cache.shape != k_cache.shape:
+        raise ValueError("cache shape mismatch")
+    if k_cache.dtype != q.dtype or v_cache.dtype != q.dtype:
+        raise ValueError("q/k/v dtype mismatch")
+    if o is None:
+        o = torch.empty_like(q)
+    if lse is None and want_lse:
+        lse = torch.empty((batch, hq, q_len), dtype=torch.float32, device=q.device)
+    mk = kv_idx.shape[1] if kv_idx is not None else 0
+    if kv_idx is not None and kv_cnt.shape[0] * pattern.block < q_start + q_len:
+        raise ValueError("block lists shorter than the context")
+    st = lib().powattn_prefill_chunk(ctypes.byref(pattern.c()), _ptr(kv_cnt), _ptr(kv_idx), mk,
+                                     _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(o), _ptr(lse),
+                                     batch, hq, hkv, int(q_start), q_len, cap, d, _dtype_code(q),
+                                     float(softmax_scale), _stream(stream))
+    _check(st, "powattn_prefill_chunk")
     return o, lse
 
 

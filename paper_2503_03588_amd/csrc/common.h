@@ -18,8 +18,10 @@ struct pa_prefill_args {
   int32_t max_k;
   const void* q; const void* k; const void* v; void* o; float* lse;
   int32_t batch, hq, hkv;
-  int64_t seq_len;
-  int32_t nb;      // ceil(seq_len / block)
+  int64_t seq_len;   // keys in the context (q_start + rows of Q)
+  int64_t q_start;   // position of the first query row; 0 for a whole-sequence prefill
+  int64_t kv_rows;   // rows per (batch, KV head) slab of K/V: seq_len, or the capacity of a cache
+  int32_t nb;      // query blocks: ceil((seq_len - q_start) / block)
   int32_t head_dim;
   float scale;     // softmax scale (natural units)
   hipStream_t stream;

@@ -81,7 +81,11 @@ struct bf16_params {
   int32_t per_xcd;   // work items per XCD partition
   int32_t chain;     // items may be chained in persistent workgroups
   int64_t total_wg;
-  int64_t N;
+  int64_t N;         // keys in the context: query q_start + r attends keys <= q_start + r, all of them < N
+  int64_t q_start;   // position of the first query row of Q/O (a multiple of B); 0 for a whole-sequence prefill
+  int64_t q_rows;    // rows of Q/O per head (N - q_start)
+  int64_t kv_rows;   // rows per (batch, KV head) slab of K/V (N, or the capacity of a cache)
+  int32_t i0;        // first query block: q_start / B
   float c2;          // softmax scale * log2(e)
 };
 
@@ -164,7 +168,7 @@ void pa_prefill_bf16_kernel(bf16_params p) {
   // following ones by adding the stride nslots digit by digit with carries: all scalar, no division in the loop.
   struct item_t { int chunk, r, kvh, b, i, subs_diag; };
   auto finish_item = [&](item_t& it) {
-    it.i = p.nb - 1 - it.r;
+    it.i = p.i0 + p.nb - 1 - it.r;
     // tiles of the diagonal block needed by any wavefront of the item
     int last_task = it.chunk * NW + NW - 1;
     if (last_task > p.tasks - 1) last_task = p.tasks - 1;
@@ -287,8 +291,8 @@ void pa_prefill_bf16_kernel(bf16_params p) {
     c_k = k; c_pos = 0;
     c_ntiles = p.dense ? it.i * p.subs + it.subs_diag : __builtin_amdgcn_readfirstlane(s_cnt[k & 1][0]);
     c_steps = (k + 1 < n_items && c_ntiles < MIN_STEPS) ? MIN_STEPS : c_ntiles;
-    c_kb = p.k + (((int64_t)it.b * p.hkv + it.kvh) * p.N) * D;
-    c_vb = p.v + (((int64_t)it.b * p.hkv + it.kvh) * p.N) * D;
+    c_kb = p.k + (((int64_t)it.b * p.hkv + it.kvh) * p.kv_rows) * D;
+    c_vb = p.v + (((int64_t)it.b * p.hkv + it.kvh) * p.kv_rows) * D;
   };
   // Prepares the next fill of the stream.  After the end of the stream the fills go on, re-reading the first
   // tile of the last item into stages nobody reads: every step then issues the same number of copies, and
@@ -314,7 +318,7 @@ void pa_prefill_bf16_kernel(bf16_params p) {
     const bool act = task < p.tasks;
     const int g = act ? task / slices : 0, sl = act ? task % slices : 0;
     const int64_t tok = (int64_t)it.i * p.B + sl * QW + ln;
-    const __bf16* qrow = p.q + (((int64_t)it.b * p.hq + it.kvh * p.G + g) * p.N + tok) * D;
+    const __bf16* qrow = p.q + (((int64_t)it.b * p.hq + it.kvh * p.G + g) * p.q_rows + (tok - p.q_start)) * D;
     const bool ok = act && tok < p.N;
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
@@ -656,7 +660,7 @@ void pa_prefill_bf16_kernel(bf16_params p) {
       auto quad_xor2 = [](uint32_t x) -> uint32_t { return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0x4E, 0xF, 0xF, true); };
       const int li = lane & 3;
       const int64_t tok0 = tok - li;                   // first row of the quad
-      __bf16* obase = p.o + (((int64_t)it.b * p.hq + h) * p.N + tok0) * D + hh * (D / 2) + 8 * li;
+      __bf16* obase = p.o + (((int64_t)it.b * p.hq + h) * p.q_rows + (tok0 - p.q_start)) * D + hh * (D / 2) + 8 * li;
 #pragma unroll
       for (int u = 0; u < NP / 8; ++u) {
         uint32_t c[4][4];                              // c[m][word]: chunk 4u+m of this lane's row
@@ -685,7 +689,7 @@ void pa_prefill_bf16_kernel(bf16_params p) {
         }
       }
       if (active && tok < p.N && p.lse && hh == 0)
-        p.lse[((int64_t)it.b * p.hq + h) * p.N + tok] = (m_run + log2f(ltot)) * 0.69314718055994530942f;
+        p.lse[((int64_t)it.b * p.hq + h) * p.q_rows + (tok - p.q_start)] = (m_run + log2f(ltot)) * 0.69314718055994530942f;
     }
     it = it1; it1 = it2; it2 = next_item(it2);
   }
@@ -733,6 +737,7 @@ int pa_launch_prefill_bf16(const pa_prefill_args& a) {
   if (!p.dense && (int64_t)a.max_k * p.subs > TILE_CAP) return POWATTN_UNSUPPORTED;
   if (a.seq_len > 0x7fffffffLL - 1024) return POWATTN_UNSUPPORTED;   // key positions are kept in 32 bits
   p.N = a.seq_len;
+  p.q_start = a.q_start; p.q_rows = a.seq_len - a.q_start; p.kv_rows = a.kv_rows; p.i0 = (int32_t)(a.q_start / a.pat.block);
   p.c2 = a.scale * 1.44269504088896340736f;
   const int64_t tasks = (int64_t)p.G * p.B / QW;
   if (tasks > (1 << 20)) return POWATTN_UNSUPPORTED;

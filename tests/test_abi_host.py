@@ -117,6 +117,32 @@ def _decode(L, pat=None, q=FAKE, k=FAKE, v=FAKE, kv_len=FAKE, cap=65536, o=FAKE,
                             ws, ws_bytes, None)
 
 
+def _chunk(L, pat=None, cnt=FAKE, idx=FAKE, max_k=13, q=FAKE, k=FAKE, v=FAKE, o=FAKE, lse=None,
+           batch=1, hq=4, hkv=2, q_start=1024, q_len=512, cap=4096, d=128, dtype=pa.BF16, scale=0.0):
+    cp = (pat or pa.Pattern(64, 4, 1)).c()
+    return L.powattn_prefill_chunk(ctypes.byref(cp), cnt, idx, max_k, q, k, v, o, lse, batch, hq, hkv,
+                                   q_start, q_len, cap, d, dtype, scale, None)
+
+
+def test_prefill_chunk_argument_errors(L):
+    assert _chunk(L, q=None) == pa.INVALID_ARG
+    assert _chunk(L, k=None) == pa.INVALID_ARG
+    assert _chunk(L, o=None) == pa.INVALID_ARG
+    assert _chunk(L, cnt=None) == pa.INVALID_ARG
+    assert _chunk(L, max_k=0) == pa.INVALID_ARG
+    assert _chunk(L, hq=6, hkv=4) == pa.INVALID_ARG
+    assert _chunk(L, q_start=-64) == pa.INVALID_ARG
+    assert _chunk(L, q_start=1000) == pa.INVALID_ARG             # not a multiple of the block size
+    assert _chunk(L, q_len=0) == pa.INVALID_ARG
+    assert _chunk(L, q_start=4032, q_len=128) == pa.INVALID_ARG  # runs past the cache capacity
+    assert _chunk(L, scale=float("nan")) == pa.INVALID_ARG
+    assert _chunk(L, dtype=pa.F32) == pa.UNSUPPORTED
+    assert _chunk(L, d=96) == pa.UNSUPPORTED
+    assert _chunk(L, pat=pa.Pattern(48, 4, 1), q_start=960) == pa.UNSUPPORTED
+    # the dense pattern needs no lists
+    assert _chunk(L, pat=pa.Pattern(64, 1, 0, flags=pa.DENSE), cnt=None, idx=None, max_k=0, q=None) == pa.INVALID_ARG
+
+
 def test_decode_argument_errors(L):
     assert _decode(L, q=None) == pa.INVALID_ARG
     assert _decode(L, k=None) == pa.INVALID_ARG
