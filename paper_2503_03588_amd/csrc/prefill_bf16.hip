@@ -53,6 +53,7 @@
 #include <type_traits>
 #include "common.h"
 
+
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -105,6 +106,11 @@ constexpr int TILE_CAP = 4096;   // tiles per query block with an explicit list 
 __device__ __forceinline__ void async_copy16(const void* sbase, uint32_t voff, uint32_t lds_off) {
   asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_off) : "memory");
 }
+// the same with the LDS offset given as a scalar base plus a constant
+template <int OFF>
+__device__ __forceinline__ void async_copy16_at(const void* sbase, uint32_t voff, uint32_t lds_base) {
+  asm volatile("s_add_u32 m0, %2, %3\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_base), "n"(OFF) : "memory", "scc");
+}
 
 // a wavefront-uniform pointer, forced into scalar registers
 template <typename T>
@@ -120,7 +126,9 @@ __device__ __forceinline__ void wait_vmcnt() {   // s_waitcnt vmcnt(N) only
   __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
 
-template <int D, int NW, int NS>
+// DENSE: the implicit list {0..i} instead of a block list.  CHAIN: the launch chains work items in persistent
+// workgroups (two half-size tile tables, list rows prefetched); otherwise one workgroup per item.
+template <int D, int NW, int NS, bool DENSE, bool CHAIN>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void pa_prefill_bf16_kernel(bf16_params p) {
   constexpr int ROWB = 2 * D;        // bytes per K/V row
@@ -160,8 +168,8 @@ void pa_prefill_bf16_kernel(bf16_params p) {
     if (lim > cuslot) n_items = (int)((lim - cuslot + nslots - 1) / nslots);
   }
   if (n_items == 0) return;
-  const bool chained = n_items > 1;    // tables in halves, list rows prefetched
-  const int tab_half = chained ? TILE_CAP / 2 : 0;
+  constexpr bool chained = CHAIN;      // tables in halves, list rows prefetched
+  constexpr int tab_half = CHAIN ? TILE_CAP / 2 : 0;
 
   // Items are numbered L = ((b*hkv + kvh)*nb + r)*chunks + chunk with r counting query blocks from the last one
   // down (longest rows first, which matters for the dense list).  The first item is decoded by division, the
@@ -217,6 +225,7 @@ void pa_prefill_bf16_kernel(bf16_params p) {
       w += it.subs_diag;
     }
     if (lane == 0) s_cnt[tab][0] = w;
+    if (w == 0 && lane == 0) s_tile[tab * tab_half] = 0;   // an empty row still has an entry to look up
   };
   auto table_from_memory = [&](int tab, const item_t& it) {          // first wavefront
     int n = p.kv_cnt[it.i];
@@ -245,7 +254,7 @@ void pa_prefill_bf16_kernel(bf16_params p) {
   // that all of them count the same number of outstanding copies; only the first one's copy is read).
   auto copy_row = [&](const item_t& it) {
     const int32_t* src = reinterpret_cast<const int32_t*>(p.k);      // dense: a dummy 4-byte read
-    if (!p.dense) {
+    if (!DENSE) {
       const int e = lane < p.max_k ? lane : p.max_k - 1;
       src = lane == 63 ? p.kv_cnt + it.i : p.kv_idx + (int64_t)it.i * p.max_k + e;
     }
@@ -262,7 +271,12 @@ void pa_prefill_bf16_kernel(bf16_params p) {
   const __bf16* f_vt = p.v;
   int f_lim = 0;
   uint32_t f_dst = 0;
-  auto fill_prep = [&](const __bf16* kbase, const __bf16* vbase, int key0, int stage) {
+  const uint32_t w_dst = __builtin_amdgcn_readfirstlane(lds0 + wave * IPW * SRB);   // this wavefront's share of stage 0
+  int f_row[IPW];                                      // this lane's row in each of the wavefront's copy instructions
+#pragma unroll
+  for (int x = 0; x < IPW; ++x) f_row[x] = RPI * (wave * IPW + x) + cp_row;
+  const uint32_t f_chunk = (uint32_t)cp_chunk << 4;
+  auto fill_prep = [&](const __bf16* kbase, const __bf16* vbase, int key0, uint32_t dst) {
     // ragged tail: rows beyond the sequence repeat its last row (they are masked, but must be finite)
     const int last = (int)p.N - 1;
     const int k0 = key0 < last ? key0 : last;
@@ -270,41 +284,67 @@ void pa_prefill_bf16_kernel(bf16_params p) {
     // (scalar values may live in vector registers when scalar registers are short: pin the bases down)
     f_kt = uniform_ptr(kbase + (int64_t)k0 * D);
     f_vt = uniform_ptr(vbase + (int64_t)k0 * D);
-    f_dst = lds0 + stage * STAGEB;
+    f_dst = dst;
   };
-  auto fill_part = [&](int j) {                        // copy j of LPT: instruction x = j/2 of this wavefront, K then V
-    const int inst = wave * IPW + (j >> 1);            // rows RPI*inst .. +RPI-1 of the tile
-    int row = RPI * inst + cp_row;
+  auto fill_copy = [&](auto jc) {                      // copy j of LPT: instruction x = j/2 of this wavefront, K then V
+    constexpr int j = decltype(jc)::value;
+    int row = f_row[j >> 1];                           // rows RPI*inst .. +RPI-1 of the tile, inst = wave*IPW + j/2
     row = row < f_lim ? row : f_lim;
-    const uint32_t voff = (uint32_t)row * ROWB + (cp_chunk << 4);
-    const uint32_t dst = f_dst + inst * SRB + (j & 1) * TILEB;
-    async_copy16((j & 1) ? f_vt : f_kt, voff, __builtin_amdgcn_readfirstlane(dst));
+    const uint32_t voff = (uint32_t)row * ROWB | f_chunk;
+    if (j & 1) async_copy16_at<(j >> 1) * SRB + TILEB>(f_vt, voff, f_dst);
+    else async_copy16_at<(j >> 1) * SRB>(f_kt, voff, f_dst);
+  };
+  static_assert(LPT <= 8, "fill_part lists the copies");
+  auto fill_part = [&](int j) {                        // j is a constant wherever this is called (unrolled loops)
+    switch (j) {
+      case 0: fill_copy(std::integral_constant<int, 0>{}); break;
+      case 1: fill_copy(std::integral_constant<int, 1 % LPT>{}); break;
+      case 2: fill_copy(std::integral_constant<int, 2 % LPT>{}); break;
+      case 3: fill_copy(std::integral_constant<int, 3 % LPT>{}); break;
+      case 4: fill_copy(std::integral_constant<int, 4 % LPT>{}); break;
+      case 5: fill_copy(std::integral_constant<int, 5 % LPT>{}); break;
+      case 6: fill_copy(std::integral_constant<int, 6 % LPT>{}); break;
+      default: fill_copy(std::integral_constant<int, 7 % LPT>{}); break;
+    }
   };
 
   // ---- the tile stream: a cursor runs NS-1 fills ahead of the compute, across item boundaries ----
   // An item that has a successor lasts at least MIN_STEPS steps (short rows are padded with fills that nobody
   // reads), so the cursor is never more than one item ahead and two tables are enough.
-  int c_k = 0, c_pos = 0, c_ntiles = 0, c_steps = 0, c_stage = 0;
+  int c_k = 0, c_pos = 0, c_ntiles = 0, c_steps = 0, c_last = 0;
+  uint32_t c_dst = w_dst;       // this wavefront's share of the stage the next fill goes to
+  uint32_t c_tab = 0;           // LDS address of the table the cursor reads
+  int pref_key = 0;             // table entry of the cursor's position, read from LDS one fill ahead of its use
   const __bf16* c_kb = p.k;
   const __bf16* c_vb = p.v;
   auto cursor_enter = [&](int k, const item_t& it) {
     c_k = k; c_pos = 0;
-    c_ntiles = p.dense ? it.i * p.subs + it.subs_diag : __builtin_amdgcn_readfirstlane(s_cnt[k & 1][0]);
+    c_ntiles = DENSE ? it.i * p.subs + it.subs_diag : __builtin_amdgcn_readfirstlane(s_cnt[k & 1][0]);
+    c_last = c_ntiles > 0 ? c_ntiles - 1 : 0;
+    if (!DENSE) {
+      c_tab = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) int*)&s_tile[(k & 1) * tab_half]);
+      pref_key = s_tile[(k & 1) * tab_half];
+    }
     c_steps = (k + 1 < n_items && c_ntiles < MIN_STEPS) ? MIN_STEPS : c_ntiles;
     c_kb = p.k + (((int64_t)it.b * p.hkv + it.kvh) * p.kv_rows) * D;
     c_vb = p.v + (((int64_t)it.b * p.hkv + it.kvh) * p.kv_rows) * D;
   };
-  // Prepares the next fill of the stream.  After the end of the stream the fills go on, re-reading the first
+  // Prepares the next fill of the stream.  After the end of the stream the fills go on, re-reading the last
   // tile of the last item into stages nobody reads: every step then issues the same number of copies, and
-  // the waits can count them.
+  // the waits can count them.  The table entry of a fill is read from LDS during the previous fill, so that
+  // its latency is not exposed right after the step's barrier.
   auto next_fill = [&]() {
     if (c_pos >= c_steps && c_k + 1 < n_items)
       cursor_enter(c_k + 1, it1);      // the cursor is never more than one item ahead of the compute
-    int key0 = 0;
-    if (c_pos < c_ntiles) key0 = p.dense ? c_pos * KT : __builtin_amdgcn_readfirstlane(s_tile[(c_k & 1) * tab_half + c_pos]);
-    fill_prep(c_kb, c_vb, key0, c_stage);
-    c_stage = c_stage == NS - 1 ? 0 : c_stage + 1;
+    // Beyond the tiles of the row (padding steps, and after the end of the stream) the last tile is copied again.
+    int key0;
+    if (DENSE) key0 = (c_pos < c_last ? c_pos : c_last) * KT;
+    else key0 = __builtin_amdgcn_readfirstlane(pref_key);
+    fill_prep(c_kb, c_vb, key0, c_dst);
+    c_dst = c_dst == w_dst + (NS - 1) * STAGEB ? w_dst : c_dst + STAGEB;
     ++c_pos;
+    if (!DENSE)
+      pref_key = *reinterpret_cast<const __attribute__((address_space(3))) int*>((uintptr_t)(c_tab + 4 * (uint32_t)(c_pos < c_last ? c_pos : c_last)));
   };
   auto fill_all = [&]() {
 #pragma unroll
@@ -332,10 +372,10 @@ void pa_prefill_bf16_kernel(bf16_params p) {
   finish_item(it);
   it1 = next_item(it);
   it2 = next_item(it1);
-  if (!p.dense) {
+  if (!DENSE) {
     if (wave == 0) {
       table_from_memory(0, it);
-      if (chained) table_from_memory(1, it1);
+      if (chained && n_items > 1) table_from_memory(1, it1);
     }
     __syncthreads();
   }
@@ -348,21 +388,24 @@ void pa_prefill_bf16_kernel(bf16_params p) {
   // va inside the stage whose V tile is multiplied next; they are advanced in place from stage to stage.
   // K fragment (d-step c, key half rt) of lane (ln, hh): row 32rt + ln, chunk 2c + hh.
   constexpr int K_C = 32 * RPI, K_RT = (32 / RPI) * SRB;                 // offsets per d-step and per key half
-  uint32_t ka = lds0 + (ln / RPI) * SRB + ((hh * RPI + ln % RPI) << 4);
+  const uint32_t ka0 = lds0 + (ln / RPI) * SRB + ((hh * RPI + ln % RPI) << 4);
   // V^T fragment (16-key step kk, d tile dt): two transposing reads, rows 16kk + r4 and 16kk + r4 + 8,
   // chunk 4dt + x, 8-byte half lane&1
   constexpr int V_KK = (16 / RPI) * SRB, V_DT = 4 * RPI * 16, V_HI = (8 / RPI) * SRB;
-  uint32_t va;
+  uint32_t va0;
   {
     const int r4 = 4 * hh + ((lane & 15) >> 2);              // row of the first read inside a 16-key step
     const int x = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1); // chunk inside the 32-wide d tile
-    va = lds0 + TILEB + (r4 / RPI) * SRB + ((x * RPI + r4 % RPI) << 4) + 8 * (lane & 1);
+    va0 = lds0 + TILEB + (r4 / RPI) * SRB + ((x * RPI + r4 % RPI) << 4) + 8 * (lane & 1);
   }
-  int k_stage = 0, v_stage = 0;       // ring stages ka and va point into
-  auto advance = [&](uint32_t& addr, int& stage) {
-    addr += stage == NS - 1 ? (uint32_t)(-(NS - 1) * STAGEB) : (uint32_t)STAGEB;
-    stage = stage == NS - 1 ? 0 : stage + 1;
+  // One scalar ring offset serves both: K(t+1) sits one stage after V(t), so ka moves on at the start of a step
+  // and va catches up with it at the end.
+  uint32_t ka = ka0, va = va0, ring_off = 0;
+  auto advance_k = [&]() {
+    ring_off = ring_off == (NS - 1) * STAGEB ? 0u : ring_off + STAGEB;
+    ka = ka0 + ring_off;
   };
+  auto advance_v = [&]() { va = va0 + ring_off; };
 
   // ---- pieces of the pipeline ----
   constexpr int NSLOT = 2 * NC + 4 * ND;   // matrix instructions per tile: 32 at head_dim 128, 16 at 64
@@ -424,7 +467,7 @@ void pa_prefill_bf16_kernel(bf16_params p) {
     q_in_blk = sl * QW;
     const int64_t q0 = (int64_t)it.i * p.B + q_in_blk;
     int n_tiles, n_before;
-    if (p.dense) {
+    if (DENSE) {
       n_before = it.i * p.subs;               // blocks 0..i-1 in full, then the needed part of block i
       n_tiles = n_before + it.subs_diag;
     } else {
@@ -452,7 +495,7 @@ void pa_prefill_bf16_kernel(bf16_params p) {
     // ---- look-ahead: the table of the next item from its prefetched list row (the first two tables were
     // built above), and the copy of the row of the item after it ----
     if (chained) {
-      if (!p.dense && wave == 0 && k >= 1 && more) table_from_row((k + 1) & 1, it1);
+      if (!DENSE && wave == 0 && k >= 1 && more) table_from_row((k + 1) & 1, it1);
       copy_row(k + 2 < n_items ? it2 : it);
     }
 
@@ -467,7 +510,7 @@ void pa_prefill_bf16_kernel(bf16_params p) {
     // same o and lse as long as exp2(s - m) stays in range.  It is raised only when a score exceeds it by
     // more than RESCALE_TAU (p <= 2^tau), which makes the rescaling of O (64 multiplies per lane) a
     // rare, wavefront-uniform branch instead of a per-tile cost.
-    f32x16 Sc[2];
+    f32x16 Sc[2], Sd[2];     // scores of the current tile; the steps alternate between the two
     u32x4 P0;
     float m_run = -INFINITY, l_run = 0.f;
     if (n_my > 0) {
@@ -504,12 +547,11 @@ void pa_prefill_bf16_kernel(bf16_params p) {
     // exponentials of elements 0..7 of S(t+1).  The source order IS the schedule: a scheduling barrier after
     // every matrix instruction keeps the compiler from regrouping the stream into a matrix phase and a
     // vector phase.  `masked` selects the variant that applies the causal mask to S(t+1).
-    auto step = [&](int t, auto masked) {
+    auto step = [&](int t, auto masked, f32x16 (&Sc)[2], f32x16 (&Sn)[2]) {
       constexpr bool MASKED = decltype(masked)::value;
-      advance(ka, k_stage);               // K(t+1) sits one stage after V(t)
+      advance_k();               // K(t+1) sits one stage after V(t)
       top(t);
       bf16x8 fr[NSLOT];
-      f32x16 Sn[2];
       u32x4 Pk[4], Pn;
       Pk[0] = P0;
       float pe[32], pn[8];
@@ -526,17 +568,25 @@ void pa_prefill_bf16_kernel(bf16_params p) {
 #pragma unroll
         for (int vs = sl2 * VPS; vs < (sl2 + 1) * VPS; ++vs) {
           if (vs < 18) {
+            // An exponential's result may not be read by the instruction right after it, so the sum and the
+            // packing of an element trail its exponential by one element: the exponential ends the portion.
 #pragma unroll
             for (int e = (4 * vs) / 3; e < (4 * (vs + 1)) / 3; ++e) {
               const int rg = 8 + e;
+              if (rg > 8) {
+                rs += pe[rg - 1];
+                if (!(rg & 1)) Pk[(rg - 1) >> 3][((rg - 1) & 7) >> 1] = pack2(pe[rg - 2], pe[rg - 1]);
+              }
               pe[rg] = pexp(Sc, rg, m_run);
-              rs += pe[rg];
-              if (rg & 1) Pk[rg >> 3][(rg & 7) >> 1] = pack2(pe[rg - 1], pe[rg]);
             }
             if (MASKED && vs == 17) mask(Sn, (t + 1 - n_before) * KT);
           } else if (vs < 21) {
             constexpr int lo[3] = {0, 11, 22}, hi[3] = {11, 22, 32};
-            if (vs == 18) mx = Sn[0][0];
+            if (vs == 18) {
+              rs += pe[31];
+              Pk[3][3] = pack2(pe[30], pe[31]);
+              mx = Sn[0][0];
+            }
 #pragma unroll
             for (int rg = lo[vs - 18]; rg < hi[vs - 18]; ++rg) mx = fmaxf(mx, Sn[rg >> 4][rg & 15]);
           } else if (vs == 21) {
@@ -544,17 +594,21 @@ void pa_prefill_bf16_kernel(bf16_params p) {
             raise = mx > m_run + RESCALE_TAU;
           } else if (vs == 22) {
             m_new = raise ? mx : m_run;
-            alpha = __builtin_amdgcn_exp2f(m_run - m_new);
           } else if (vs < 29) {
 #pragma unroll
             for (int rg = (4 * (vs - 23)) / 3; rg < (4 * (vs - 22)) / 3; ++rg) {
+              if (rg > 0) {
+                rs_n += pn[rg - 1];
+                if (!(rg & 1)) Pn[(rg - 1) >> 1] = pack2(pn[rg - 2], pn[rg - 1]);
+              }
               pn[rg] = pexp(Sn, rg, m_new);
-              rs_n += pn[rg];
-              if (rg & 1) Pn[rg >> 1] = pack2(pn[rg - 1], pn[rg]);
             }
+          } else if (vs == 29) {
+            rs_n += pn[7];
+            Pn[3] = pack2(pn[6], pn[7]);
             // results that are only used by the next step: keep their computation here, in the shadow of
             // the matrix instructions, instead of letting it sink to the end of the iteration
-            if (vs == 28) asm volatile("" ::"v"(Pn), "v"(rs_n));
+            asm volatile("" ::"v"(Pn), "v"(rs_n));
           }
         }
         // ---- the matrix instruction: within a pair the second one goes first, because it waits for the pair's
@@ -572,6 +626,7 @@ void pa_prefill_bf16_kernel(bf16_params p) {
       }
       l_run += rs;
       if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+        alpha = __builtin_amdgcn_exp2f(m_run - m_new);     // 1 in the lanes that keep their reference point
         l_run *= alpha;
 #pragma unroll
         for (int dt = 0; dt < ND; ++dt)
@@ -580,9 +635,8 @@ void pa_prefill_bf16_kernel(bf16_params p) {
       }
       l_run += rs_n;
       m_run = m_new;
-      Sc[0] = Sn[0]; Sc[1] = Sn[1];
       P0 = Pn;
-      advance(va, v_stage);
+      advance_v();
     };
     // Only the last tile a wavefront computes needs the mask: the diagonal tiles before it lie entirely
     // below its first query.  Every wavefront runs n_steps iterations (the barriers are shared): plain
@@ -592,11 +646,13 @@ void pa_prefill_bf16_kernel(bf16_params p) {
     if (t_mask > n_my) t_mask = n_my;
     const int T1 = t_mask > 1 ? t_mask - 1 : 0, T2 = n_my > 1 ? n_my - 1 : 0;
     int t = 0;
-    for (; t < T1; ++t) step(t, std::false_type{});
-    for (; t < T2; ++t) step(t, std::true_type{});
+    // two steps per trip, the second with the roles of the score registers exchanged: no copies
+    for (; t + 1 < T1; t += 2) { step(t, std::false_type{}, Sc, Sd); step(t + 1, std::false_type{}, Sd, Sc); }
+    for (; t < T1; ++t) { step(t, std::false_type{}, Sc, Sd); Sc[0] = Sd[0]; Sc[1] = Sd[1]; }
+    for (; t < T2; ++t) { step(t, std::true_type{}, Sc, Sd); Sc[0] = Sd[0]; Sc[1] = Sd[1]; }
     for (; t < n_my; ++t) {
       // ---- last tile of this wavefront: the rest of P(t), O += P(t) V(t) ----
-      advance(ka, k_stage);
+      advance_k();
       top(t);
       fill_all();
       if (more && t == n_steps - 1) load_q(it1);
@@ -614,14 +670,14 @@ void pa_prefill_bf16_kernel(bf16_params p) {
         const int kk = (sl2 - 2 * NC) / ND, dt = (sl2 - 2 * NC) % ND;
         O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(load_frag(sl2), __builtin_bit_cast(bf16x8, Pk[kk]), O[dt], 0, 0, 0);
       }
-      advance(va, v_stage);
+      advance_v();
     }
     for (; t < n_steps; ++t) {
-      advance(ka, k_stage);
+      advance_k();
       top(t);
       fill_all();
       if (more && t == n_steps - 1) load_q(it1);
-      advance(va, v_stage);
+      advance_v();
     }
 
     // ---- epilogue ----
@@ -697,12 +753,12 @@ void pa_prefill_bf16_kernel(bf16_params p) {
   wait_vmcnt<0>();
 }
 
-template <int D, int NW, int NS>
-int launch(const bf16_params& p, hipStream_t stream) {
+template <int D, int NW, int NS, bool DENSE, bool CHAIN>
+int launch_as(const bf16_params& p, hipStream_t stream) {
   constexpr size_t lds = (size_t)NS * 2 * (KT / (512 / D)) * (1024 + 16 * (512 / D));
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pa_prefill_bf16_kernel<D, NW, NS>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pa_prefill_bf16_kernel<D, NW, NS, DENSE, CHAIN>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return pa_note_hip(e);
     attr_done = true;
@@ -710,7 +766,7 @@ int launch(const bf16_params& p, hipStream_t stream) {
   // One workgroup per work item, or, when the items can be chained (the block lists are short enough for the
   // look-ahead tables and registers), one persistent workgroup per compute unit that walks through its share.
   int64_t grid = (int64_t)p.per_xcd * 8;
-  if (p.chain) {
+  if (CHAIN) {
     static int n_cu[64] = {0};
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
@@ -722,11 +778,18 @@ int launch(const bf16_params& p, hipStream_t stream) {
     const int64_t persistent = (int64_t)(n_cu[dev] / 8) * 8;
     if (grid > persistent) grid = persistent;
   }
-  hipLaunchKernelGGL((pa_prefill_bf16_kernel<D, NW, NS>), dim3((uint32_t)grid), dim3(64 * NW), lds, stream, p);
+  hipLaunchKernelGGL((pa_prefill_bf16_kernel<D, NW, NS, DENSE, CHAIN>), dim3((uint32_t)grid), dim3(64 * NW), lds, stream, p);
   return pa_note_hip(hipGetLastError());
 }
 
+template <int D, int NW, int NS>
+int launch(const bf16_params& p, hipStream_t stream) {
+  if (p.dense) return launch_as<D, NW, NS, true, true>(p, stream);     // the implicit list is always chained
+  return p.chain ? launch_as<D, NW, NS, false, true>(p, stream) : launch_as<D, NW, NS, false, false>(p, stream);
+}
+
 }  // namespace
+
 
 int pa_launch_prefill_bf16(const pa_prefill_args& a) {
   bf16_params p;
