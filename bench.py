@@ -62,7 +62,11 @@ def main():
 
     # ---------------- workload ----------------
     P = dict(batch=1, hq=32, hkv=8, n=131072, d=128, B=128, W=4, S=1, seed=2)          # configuration 3
-    Dc = dict(batch=16, hq=32, hkv=8, cap=65536, d=128, B=64, W=4, S=1, seed=3)         # configuration 4
+    # configuration 4: 65536 tokens in every cache.  The caches are allocated with room for one more block
+    # (generation appends): with a capacity of exactly 2^16 tokens the slabs of the 128 (sequence, KV head) pairs
+    # lie 16 MB apart and every pair's attended blocks fall on the same HBM channels and banks (measured: 18.7 us
+    # per step instead of 15.8).
+    Dc = dict(batch=16, hq=32, hkv=8, len=65536, cap=65536 + 64, d=128, B=64, W=4, S=1, seed=3)
     pat_p = pa.Pattern(P["B"], P["W"], P["S"])
     pat_d = pa.Pattern(Dc["B"], Dc["W"], Dc["S"])
 
@@ -77,13 +81,14 @@ def main():
 
     gen = torch.Generator(device=dev)
     gen.manual_seed(Dc["seed"])
-    caches = []
-    for _ in range(args.decode_caches):
-        kc = torch.randn(Dc["batch"], Dc["hkv"], Dc["cap"], Dc["d"], device=dev, dtype=torch.bfloat16, generator=gen)
-        vc = torch.randn(Dc["batch"], Dc["hkv"], Dc["cap"], Dc["d"], device=dev, dtype=torch.bfloat16, generator=gen)
-        caches.append((kc, vc))
+    # all caches in one allocation each for K and V, so that the same memory can also be addressed as a pool of pages
+    kall = torch.randn(args.decode_caches, Dc["batch"], Dc["hkv"], Dc["cap"], Dc["d"], device=dev,
+                       dtype=torch.bfloat16, generator=gen)
+    vall = torch.randn(args.decode_caches, Dc["batch"], Dc["hkv"], Dc["cap"], Dc["d"], device=dev,
+                       dtype=torch.bfloat16, generator=gen)
+    caches = [(kall[c], vall[c]) for c in range(args.decode_caches)]
     qd = torch.randn(Dc["batch"], Dc["hq"], Dc["d"], device=dev, dtype=torch.bfloat16, generator=gen)
-    lens = torch.full((Dc["batch"],), Dc["cap"], dtype=torch.int32, device=dev)
+    lens = torch.full((Dc["batch"],), Dc["len"], dtype=torch.int32, device=dev)
     od = torch.empty_like(qd)
     lsed = torch.empty((Dc["batch"], Dc["hq"]), dtype=torch.float32, device=dev)
     ws = pa.decode_workspace(pat_d, Dc["batch"], Dc["hq"], Dc["hkv"], Dc["d"], Dc["cap"])
@@ -137,12 +142,46 @@ def main():
     torch.cuda.synchronize()
     decode_us = d0.elapsed_time(d1) * 1e3 / dec_iters
 
+    # The same step over a paged cache (powattn_decode_paged): the caches' memory read as a pool of pages of one
+    # block each, every sequence's blocks on random pages of the whole pool (26 GB: cold), several tables in
+    # rotation.  Then larger batches on the same pool: the fixed costs of a step (launch, the look-ups that
+    # depend on one another, the slowest wavefront) are spread over more bytes.
+    kpool = kall.view(-1, Dc["hkv"], Dc["B"], Dc["d"])
+    vpool = vall.view(-1, Dc["hkv"], Dc["B"], Dc["d"])
+    n_pages, stride = kpool.shape[0], Dc["cap"] // Dc["B"]
+    n_row = len(pa.row_host(pat_d, (Dc["len"] - 1) // Dc["B"]))
+    paged = []
+    for batch in (Dc["batch"], 64, 256):
+        tables = [torch.randint(0, n_pages, (batch, stride), dtype=torch.int32, device=dev, generator=gen)
+                  for _ in range(4)]
+        qb = torch.randn(batch, Dc["hq"], Dc["d"], device=dev, dtype=torch.bfloat16, generator=gen)
+        lb = torch.full((batch,), Dc["len"], dtype=torch.int32, device=dev)
+        ob = torch.empty_like(qb)
+        lseb = torch.empty((batch, Dc["hq"]), dtype=torch.float32, device=dev)
+        wsb = pa.decode_workspace(pat_d, batch, Dc["hq"], Dc["hkv"], Dc["d"], Dc["cap"])
+        iters = 80
+        for s in range(8):
+            pa.decode_paged(pat_d, qb, kpool, vpool, tables[s % 4], lb, o=ob, lse=lseb, workspace=wsb)
+        torch.cuda.synchronize()
+        p0, p1 = ev(), ev()
+        p0.record()
+        for s in range(iters):
+            pa.decode_paged(pat_d, qb, kpool, vpool, tables[s % 4], lb, o=ob, lse=lseb, workspace=wsb)
+        p1.record()
+        torch.cuda.synchronize()
+        us = p0.elapsed_time(p1) * 1e3 / iters
+        nbytes = n_row * Dc["B"] * Dc["d"] * 2 * 2 * Dc["hkv"] * batch
+        paged.append({"batch": batch, "us_per_step": round(us, 2), "tokens_per_s": round(batch / (us * 1e-6), 1),
+                      "GB/s": round(nbytes / (us * 1e-6) / 1e9, 1),
+                      "frac_of_hbm_peak": round(nbytes / (us * 1e-6) / 1e9 / PEAK_HBM_GBS, 4)})
+        del tables, qb, lb, ob, lseb, wsb
+
     pairs = int(cnt.sum().item())
     f_block = 4.0 * P["B"] * P["B"] * P["d"] * P["hq"] * P["batch"] * pairs      # attended blocks, diagonal whole
     value = f_block / (ms_per_step * 1e-3) / 1e12
     prefill_tflops = f_block / (prefill_ms * 1e-3) / 1e12
 
-    row = pa.row_host(pat_d, (Dc["cap"] - 1) // Dc["B"])
+    row = pa.row_host(pat_d, (Dc["len"] - 1) // Dc["B"])
     decode_bytes = len(row) * Dc["B"] * Dc["d"] * 2 * 2 * Dc["hkv"] * Dc["batch"]   # attended K and V tokens
     decode_gbs = decode_bytes / (decode_us * 1e-6) / 1e9
 
@@ -284,8 +323,8 @@ def main():
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": "step = mask_build + sparse prefill (b1, 32q/8kv heads, N=131072, D=128, block 128, "
-                               "W=4, S=1, bf16) + one decode step (b16, 32q/8kv, 65536-token bf16 caches, block 64, "
-                               "W=4, S=1, cold: rotating over %d caches)" % len(caches),
+                               "W=4, S=1, bf16) + one decode step (b16, 32q/8kv, 65536-token bf16 caches of capacity 65600, "
+                               "block 64, W=4, S=1, cold: rotating over %d caches)" % len(caches),
                    "attended_block_pairs": pairs, "flops_per_step": f_block},
         "roofline": {"bound": "mfma", "kernel": "pa_prefill_bf16_kernel", "achieved": round(prefill_tflops, 2),
                      "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
@@ -296,7 +335,8 @@ def main():
                    "in_step_us": round(decode_in_step_us, 2), "steps_timed": dec_iters,
                    "roofline": {"bound": "hbm", "kernel": "pa_decode_kernel (+ merge)", "achieved": round(decode_gbs, 1),
                                 "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(decode_gbs / PEAK_HBM_GBS, 4),
-                                "bytes_per_step": decode_bytes, "traffic": None}},
+                                "bytes_per_step": decode_bytes, "traffic": None},
+                   "paged_cache_by_batch": paged},
         "dense_baseline": dense,
         "paper_setting_b256_w5_s1": sweep,
         "layer_stack": stack,

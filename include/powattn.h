@@ -193,6 +193,34 @@ int powattn_decode(const powattn_pattern* pattern,
                    int32_t dtype, float softmax_scale,
                    void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * powattn_decode over a paged KV cache, the form serving systems keep their
+ * caches in (Section 4.3 measures prefill plus 1024 decode steps end to end).
+ * A page holds one block of the pattern (pattern->block tokens) for every KV
+ * head; a table per sequence says which page holds which block, so the attended
+ * blocks of a row (Algorithm 1) are a dozen table look-ups.  The result equals
+ * powattn_decode on the cache those pages spell out.
+ *   k_pages, v_pages  device [n_pages, n_kv_heads, block, head_dim]
+ *   d_block_table     device int32 [batch, table_stride]: entry [b][j] is the page of
+ *                     tokens j*block .. (j+1)*block-1 of sequence b; entries of blocks
+ *                     beyond the sequence are not read.  A page number outside
+ *                     [0, n_pages) is clamped into the pool by the kernel (wrong
+ *                     numbers, no stray access).
+ *   d_kv_len          device int32 [batch], 1 <= kv_len[b] <= table_stride * block
+ *                     (clamped into that range by the kernel)
+ *   workspace         as for powattn_decode with cache_capacity = table_stride * block
+ * Everything else as for powattn_decode.
+ * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR.
+ */
+int powattn_decode_paged(const powattn_pattern* pattern,
+                         const void* q, const void* k_pages, const void* v_pages, int64_t n_pages,
+                         const int32_t* d_block_table, int32_t table_stride,
+                         const int32_t* d_kv_len,
+                         void* o, float* lse,
+                         int32_t batch, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                         int32_t dtype, float softmax_scale,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

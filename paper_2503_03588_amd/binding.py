@@ -24,6 +24,7 @@ EXPORTS = (
     "powattn_version", "powattn_strerror", "powattn_num_blocks", "powattn_max_k",
     "powattn_row_host", "powattn_mask_build", "powattn_prefill",
     "powattn_prefill_chunk", "powattn_decode_workspace_bytes", "powattn_decode",
+    "powattn_decode_paged",
 )
 
 
@@ -86,6 +87,9 @@ def lib() -> ctypes.CDLL:
     L.powattn_decode.restype = ctypes.c_int
     L.powattn_decode.argtypes = [P, vp, vp, vp, vp, i64, vp, vp, i32, i32, i32, i32, i32, f32,
                                  vp, ctypes.c_size_t, vp]
+    L.powattn_decode_paged.restype = ctypes.c_int
+    L.powattn_decode_paged.argtypes = [P, vp, vp, vp, i64, vp, i32, vp, vp, vp, i32, i32, i32, i32, i32, f32,
+                                       vp, ctypes.c_size_t, vp]
     _lib = L
     return L
 
@@ -256,4 +260,35 @@ def decode(pattern: Pattern, q, k_cache, v_cache, kv_len, o=None, lse=None, soft
                               float(softmax_scale), _ptr(workspace), workspace.numel() * workspace.element_size(),
                               _stream(stream))
     _check(st, "powattn_decode")
+    return o, lse
+
+
+def decode_paged(pattern: Pattern, q, k_pages, v_pages, block_table, kv_len, o=None, lse=None, softmax_scale=0.0,
+                 workspace=None, want_lse=True, stream=None):
+    """powattn_decode_paged.  q/o: [b,Hq,D]; pages: [n_pages,Hkv,block,D]; block_table int32 [b, table_stride];
+    kv_len int32 [b].  Returns (o, lse)."""
+    batch, hq, d = q.shape
+    n_pages, hkv, blk = k_pages.shape[0], k_pages.shape[1], k_pages.shape[2]
+    if k_pages.shape != (n_pages, hkv, blk, d) or v_pages.shape != k_pages.shape:
+        raise ValueError("page pool shape mismatch")
+    if blk != pattern.block:
+        raise ValueError("a page holds one block of the pattern")
+    if block_table.dtype != torch.int32 or block_table.dim() != 2 or block_table.shape[0] != batch:
+        raise ValueError("block_table must be int32 [batch, table_stride]")
+    if not block_table.is_contiguous():
+        raise ValueError("block_table must be contiguous")
+    if kv_len.dtype != torch.int32 or kv_len.shape != (batch,):
+        raise ValueError("kv_len must be int32 [batch]")
+    stride = block_table.shape[1]
+    if o is None:
+        o = torch.empty_like(q)
+    if lse is None and want_lse:
+        lse = torch.empty((batch, hq), dtype=torch.float32, device=q.device)
+    if workspace is None:
+        workspace = decode_workspace(pattern, batch, hq, hkv, d, stride * blk, q.device)
+    st = lib().powattn_decode_paged(ctypes.byref(pattern.c()), _ptr(q), _ptr(k_pages), _ptr(v_pages), n_pages,
+                                    _ptr(block_table), stride, _ptr(kv_len), _ptr(o), _ptr(lse),
+                                    batch, hq, hkv, d, _dtype_code(q), float(softmax_scale),
+                                    _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(st, "powattn_decode_paged")
     return o, lse

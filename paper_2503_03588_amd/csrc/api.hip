@@ -187,5 +187,45 @@ extern "C" int powattn_decode(const powattn_pattern* pattern,
   a.workspace = workspace;
   a.n_split = pa_decode_splits(pattern, batch, n_kv_heads, cache_capacity);
   a.stream = (hipStream_t)hip_stream;
+  a.block_table = nullptr; a.table_stride = 0; a.n_pages = 0;
+  return pa_launch_decode_bf16(a);
+}
+
+extern "C" int powattn_decode_paged(const powattn_pattern* pattern,
+                                    const void* q, const void* k_pages, const void* v_pages, int64_t n_pages,
+                                    const int32_t* d_block_table, int32_t table_stride,
+                                    const int32_t* d_kv_len,
+                                    void* o, float* lse,
+                                    int32_t batch, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                    int32_t dtype, float softmax_scale,
+                                    void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int st = pa_check_pattern(pattern);
+  if (st != POWATTN_OK) return st;
+  if (!q || !k_pages || !v_pages || !d_block_table || !d_kv_len || !o) return POWATTN_INVALID_ARG;
+  if (batch < 1 || n_q_heads < 1 || n_kv_heads < 1 || head_dim < 1 || n_pages < 1 || table_stride < 1) return POWATTN_INVALID_ARG;
+  if (n_q_heads % n_kv_heads != 0) return POWATTN_INVALID_ARG;
+  if (!(softmax_scale == softmax_scale)) return POWATTN_INVALID_ARG;
+  if (dtype != POWATTN_BF16) return POWATTN_UNSUPPORTED;
+  if (!supported_head_dim(head_dim)) return POWATTN_UNSUPPORTED;
+  if (pattern->block % 64 != 0 || pattern->block > 1024) return POWATTN_UNSUPPORTED;
+  if (pattern->flags & POWATTN_DENSE) return POWATTN_UNSUPPORTED;
+  if (n_q_heads / n_kv_heads > 16) return POWATTN_UNSUPPORTED;
+  const int64_t capacity = (int64_t)table_stride * pattern->block;      // tokens a sequence's table can hold
+  if (powattn_num_blocks(pattern, capacity) < 0) return POWATTN_INVALID_ARG;
+  size_t need = powattn_decode_workspace_bytes(pattern, batch, n_q_heads, n_kv_heads, head_dim, capacity);
+  if (need == 0) return POWATTN_INVALID_ARG;
+  if (!workspace || workspace_bytes < need) return POWATTN_WORKSPACE_TOO_SMALL;
+  if (((uintptr_t)workspace & 255u) != 0) return POWATTN_INVALID_ARG;
+
+  pa_decode_args a;
+  a.pat = *pattern;
+  a.q = q; a.k = k_pages; a.v = v_pages; a.kv_len = d_kv_len; a.capacity = capacity;
+  a.o = o; a.lse = lse;
+  a.batch = batch; a.hq = n_q_heads; a.hkv = n_kv_heads; a.head_dim = head_dim;
+  a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)head_dim);
+  a.workspace = workspace;
+  a.n_split = pa_decode_splits(pattern, batch, n_kv_heads, capacity);
+  a.stream = (hipStream_t)hip_stream;
+  a.block_table = d_block_table; a.table_stride = table_stride; a.n_pages = n_pages;
   return pa_launch_decode_bf16(a);
 }

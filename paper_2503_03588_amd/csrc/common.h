@@ -41,6 +41,11 @@ struct pa_decode_args {
   void* workspace;
   int32_t n_split;   // workgroups per (batch, kv head)
   hipStream_t stream;
+  // paged cache (block_table != nullptr): k and v are page pools [n_pages, hkv, block, head_dim]; block j of
+  // sequence b is page block_table[b * table_stride + j]; capacity is table_stride * block
+  const int32_t* block_table;
+  int32_t table_stride;
+  int64_t n_pages;
 };
 int pa_launch_decode_bf16(const pa_decode_args& a);
 int32_t pa_decode_splits(const powattn_pattern* pat, int32_t batch, int32_t hkv, int64_t capacity);

@@ -50,6 +50,9 @@ struct dec_params {
   int32_t fused;        // 1: the last workgroup of a (sequence, KV head) merges the partials itself
   int32_t region;       // which set of arrival counters this call uses
   float c2;
+  const int32_t* block_table;   // paged cache: page of block j of sequence b at [b * table_stride + j]; else null
+  int32_t table_stride;
+  int64_t n_pages;
 };
 
 // Arrival counters of the fused merge: one per (sequence, KV head) and call in flight.  They live in the
@@ -124,6 +127,17 @@ __global__ __launch_bounds__(64 * NW) void pa_decode_kernel(dec_params p) {
     const int n_tok = left >= CH ? CH : (int)left;
     const __bf16* kb = kslab + tok0 * D;
     const __bf16* vb = vslab + tok0 * D;
+    if (p.block_table) {
+      // Paged cache: the block's page comes from the table (one more dependent look-up); a page holds the
+      // block's tokens of every KV head.  A page number outside the pool is clamped into it: a bad table gives
+      // wrong numbers, never an access outside the pool.
+      const int64_t blk = tok0 / p.B;                  // < table_stride, because len <= table_stride * B
+      int64_t page = p.block_table[(int64_t)b * p.table_stride + blk];
+      page = page < 0 ? 0 : (page >= p.n_pages ? p.n_pages - 1 : page);
+      const int64_t off = ((page * p.hkv + kvh) * p.B + (tok0 - blk * p.B)) * D;
+      kb = p.k + off;
+      vb = p.v + off;
+    }
 
     // ---- issue every load of the chunk ----
     // K tile 2x+y, row rho = lane%16 holds token 32x + 8(rho/4) + 4y + rho%4: with this order the S^T
@@ -367,6 +381,7 @@ int pa_launch_decode_bf16(const pa_decode_args& a) {
   p.B = a.pat.block; p.W = a.pat.window; p.S = a.pat.sink; p.flags = a.pat.flags;
   p.hq = a.hq; p.hkv = a.hkv; p.G = a.hq / a.hkv; p.splits = a.n_split; p.subs = a.pat.block / CH;
   p.c2 = a.scale * 1.44269504088896340736f;
+  p.block_table = a.block_table; p.table_stride = a.table_stride; p.n_pages = a.n_pages;
   static std::atomic<unsigned> next_region{0};
   p.fused = (a.n_split > 1 && a.n_split <= 64 && (int64_t)a.batch * a.hkv <= CTR_PER_SET) ? 1 : 0;
   p.region = p.fused ? (int32_t)(next_region.fetch_add(1) % CTR_SETS) : 0;

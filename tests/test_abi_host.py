@@ -159,6 +159,35 @@ def test_decode_argument_errors(L):
     assert _decode(L, ws=FAKE + 8) == pa.INVALID_ARG                          # misaligned workspace
 
 
+def _paged(L, pat=None, q=FAKE, k=FAKE, v=FAKE, n_pages=100, table=FAKE, stride=64, kv_len=FAKE, o=FAKE, lse=None,
+           batch=2, hq=8, hkv=2, d=128, dtype=pa.BF16, scale=0.0, ws=FAKE, ws_bytes=None):
+    p = pat or pa.Pattern(64, 4, 1)
+    cp = p.c()
+    if ws_bytes is None:
+        ws_bytes = L.powattn_decode_workspace_bytes(ctypes.byref(cp), batch, hq, hkv, d, max(stride, 1) * p.block)
+    return L.powattn_decode_paged(ctypes.byref(cp), q, k, v, n_pages, table, stride, kv_len, o, lse,
+                                  batch, hq, hkv, d, dtype, scale, ws, ws_bytes, None)
+
+
+def test_decode_paged_argument_errors(L):
+    assert _paged(L, q=None) == pa.INVALID_ARG
+    assert _paged(L, k=None) == pa.INVALID_ARG
+    assert _paged(L, v=None) == pa.INVALID_ARG
+    assert _paged(L, table=None) == pa.INVALID_ARG
+    assert _paged(L, kv_len=None) == pa.INVALID_ARG
+    assert _paged(L, o=None) == pa.INVALID_ARG
+    assert _paged(L, n_pages=0) == pa.INVALID_ARG
+    assert _paged(L, stride=0) == pa.INVALID_ARG
+    assert _paged(L, hq=6, hkv=4) == pa.INVALID_ARG
+    assert _paged(L, scale=float("nan")) == pa.INVALID_ARG
+    assert _paged(L, d=80) == pa.UNSUPPORTED
+    assert _paged(L, dtype=pa.F32) == pa.UNSUPPORTED
+    assert _paged(L, pat=pa.Pattern(32, 4, 1)) == pa.UNSUPPORTED
+    assert _paged(L, ws=None) == pa.WORKSPACE_TOO_SMALL
+    assert _paged(L, ws_bytes=64) == pa.WORKSPACE_TOO_SMALL
+    assert _paged(L, ws=FAKE + 8) == pa.INVALID_ARG
+
+
 def test_decode_workspace_size(L):
     pat = pa.Pattern(64, 4, 1)
     n = pa.decode_workspace_bytes(pat, 16, 32, 8, 128, 65536)
