@@ -258,6 +258,49 @@ def decode(q, k_cache, v_cache, kv_len, pat: Pattern, scale=None):
 
 
 # --------------------------------------------------------------------------
+# Gradients of Equation 1 (the paper trains with the sparse pattern in place,
+# Section 4.1; the gradient of a softmax-weighted sum is textbook calculus)
+# --------------------------------------------------------------------------
+def attention_backward(q, k, v, do, pat: Pattern, scale=None):
+    """Gradients of L = sum(o * do) with o from `attention` (Equation 1).
+
+    With P the row-wise softmax of the masked, scaled logits S = scale * q k^T:
+      dV = P^T dO,  dP = dO V^T,  dS = P * (dP - rowsum(P * dP)),
+      dQ = scale * dS K,  dK = scale * dS^T Q.
+    KV head g receives the sum over the query heads of its group.
+    Returns dq [batch, Hq, N, D], dk, dv [batch, Hkv, N, D] in float64.
+    """
+    q, k, v, do = widen(q), widen(k), widen(v), widen(do)
+    batch, hq, n, d = q.shape
+    hkv = k.shape[1]
+    g = hq // hkv
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    allowed = token_mask(n, pat)
+    dq = np.zeros_like(q)
+    dk = np.zeros_like(k)
+    dv = np.zeros_like(v)
+    for b in range(batch):
+        for h in range(hq):
+            kh, vh = k[b, h // g], v[b, h // g]
+            s = np.where(allowed, scale * (q[b, h] @ kh.T), -np.inf)
+            p = np.exp(s - s.max(axis=1, keepdims=True))
+            p /= p.sum(axis=1, keepdims=True)
+            dp = do[b, h] @ vh.T
+            ds = p * (dp - (p * dp).sum(axis=1, keepdims=True))
+            dq[b, h] = scale * (ds @ kh)
+            dk[b, h // g] += scale * (ds.T @ q[b, h])
+            dv[b, h // g] += p.T @ do[b, h]
+    return dq, dk, dv
+
+
+def column_lists(seq_len: int, pat: Pattern):
+    """For every key block j, the query blocks that attend it, ascending (the columns of the block mask)."""
+    bm = block_mask(seq_len, pat)
+    return [np.nonzero(bm[:, j])[0].astype(np.int64) for j in range(bm.shape[1])]
+
+
+# --------------------------------------------------------------------------
 # Work counts used by the bench's FLOP accounting
 # --------------------------------------------------------------------------
 def attended_pairs(seq_len: int, pat: Pattern) -> int:
