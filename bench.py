@@ -241,6 +241,28 @@ def main():
     # 4 KV heads, 64K context, block 64, fresh random Q/K/V per layer (no projection weights exist, so the layers
     # are not chained); per-layer kernel time.  Second pass: the hybrid schedule of Section 4.3, in which 2 of
     # every 7 layers keep full attention.  Outside the timed region. ----------------
+    # ---------------- gradients (powattn_backward) at the 128K workload: dQ, dK, dV from dO.  FLOPs as the five
+    # products of the definition (S, dP, dV, dQ, dK) over the attended block pairs: 2.5 x the forward count; the
+    # kernels compute S and dP twice (once per pass), which is not counted. ----------------
+    backward = None
+    if not args.no_dense:
+        dog = torch.randn(qg.shape, device=dev, dtype=torch.bfloat16, generator=gen)
+        dqg, dkg, dvg = torch.empty_like(qg), torch.empty_like(kg), torch.empty_like(vg)
+        wsb = torch.empty((pa.backward_workspace_bytes(pat_p, P["batch"], P["hq"], P["hkv"], P["n"], P["d"]),),
+                          dtype=torch.uint8, device=dev)
+        pa.backward(pat_p, cnt, idx, qg, kg, vg, og, lseg, dog, dq=dqg, dk=dkg, dv=dvg, workspace=wsb)
+        torch.cuda.synchronize()
+        b0, b1 = ev(), ev()
+        b0.record()
+        for _ in range(3):
+            pa.backward(pat_p, cnt, idx, qg, kg, vg, og, lseg, dog, dq=dqg, dk=dkg, dv=dvg, workspace=wsb)
+        b1.record()
+        torch.cuda.synchronize()
+        bms = b0.elapsed_time(b1) / 3
+        backward = {"ms": round(bms, 3), "tflops_5_products": round(2.5 * f_block / (bms * 1e-3) / 1e12, 1),
+                    "over_forward": round(bms / prefill_ms, 2)}
+        del dog, dqg, dkg, dvg, wsb
+
     stack = None
     if not args.no_dense:
         Ls = dict(layers=28, hq=28, hkv=4, n=65536, d=128, B=64, W=4, S=1)
@@ -340,6 +362,7 @@ def main():
         "dense_baseline": dense,
         "paper_setting_b256_w5_s1": sweep,
         "layer_stack": stack,
+        "backward_128k": backward,
         "parity": parity,
     }
     print(json.dumps(out))

@@ -221,6 +221,37 @@ int powattn_decode_paged(const powattn_pattern* pattern,
                          int32_t dtype, float softmax_scale,
                          void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Gradients of powattn_prefill (Equation 1, Section 3.1; the paper trains with
+ * the pattern in place, Section 4.1): given dO, the inputs, the output and the
+ * log-sum-exp of a whole-sequence powattn_prefill call, writes
+ *   dQ = scale * dS K,  dK = scale * dS^T Q,  dV = P^T dO,
+ *   P = exp(scale * Q K^T - lse) on attended pairs, dS = P * (dO V^T - rowsum(dO * O)),
+ * the gradients of sum(O * dO).  dK and dV of a KV head sum over its query heads.
+ *   d_kv_cnt, d_kv_idx, max_k   the lists powattn_mask_build wrote for this pattern and
+ *                  seq_len (dQ walks the rows; dK/dV walk the columns, which are
+ *                  generated from the pattern in closed form, so the lists must be
+ *                  the pattern's own: max_k < powattn_max_k is refused)
+ *   q, o, d_o, dq  device [batch, n_q_heads, seq_len, head_dim]
+ *   k, v, dk, dv   device [batch, n_kv_heads, seq_len, head_dim]
+ *   lse            device float [batch, n_q_heads, seq_len], as written by powattn_prefill
+ *   dtype          POWATTN_BF16 only; head_dim 64 or 128; block 64, 128 or 256; not POWATTN_DENSE
+ *   workspace      device, powattn_backward_workspace_bytes(...) bytes, 256-byte aligned,
+ *                  contents on entry ignored (rowsum(dO * O), and fp32 sums for the sink
+ *                  blocks, whose columns are cut into parts that add up with atomics:
+ *                  the last bits of the sink rows of dK/dV depend on the order of arrival)
+ * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR.
+ */
+size_t powattn_backward_workspace_bytes(const powattn_pattern* pattern, int32_t batch, int32_t n_q_heads,
+                                        int32_t n_kv_heads, int64_t seq_len, int32_t head_dim);
+int powattn_backward(const powattn_pattern* pattern,
+                     const int32_t* d_kv_cnt, const int32_t* d_kv_idx, int32_t max_k,
+                     const void* q, const void* k, const void* v, const void* o, const float* lse,
+                     const void* d_o, void* dq, void* dk, void* dv,
+                     int32_t batch, int32_t n_q_heads, int32_t n_kv_heads, int64_t seq_len,
+                     int32_t head_dim, int32_t dtype, float softmax_scale,
+                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,7 @@ EXPORTS = (
     "powattn_version", "powattn_strerror", "powattn_num_blocks", "powattn_max_k",
     "powattn_row_host", "powattn_mask_build", "powattn_prefill",
     "powattn_prefill_chunk", "powattn_decode_workspace_bytes", "powattn_decode",
-    "powattn_decode_paged",
+    "powattn_decode_paged", "powattn_backward_workspace_bytes", "powattn_backward",
 )
 
 
@@ -90,6 +90,11 @@ def lib() -> ctypes.CDLL:
     L.powattn_decode_paged.restype = ctypes.c_int
     L.powattn_decode_paged.argtypes = [P, vp, vp, vp, i64, vp, i32, vp, vp, vp, i32, i32, i32, i32, i32, f32,
                                        vp, ctypes.c_size_t, vp]
+    L.powattn_backward_workspace_bytes.restype = ctypes.c_size_t
+    L.powattn_backward_workspace_bytes.argtypes = [P, i32, i32, i32, i64, i32]
+    L.powattn_backward.restype = ctypes.c_int
+    L.powattn_backward.argtypes = [P, vp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i64, i32, i32,
+                                   f32, vp, ctypes.c_size_t, vp]
     _lib = L
     return L
 
@@ -292,3 +297,43 @@ def decode_paged(pattern: Pattern, q, k_pages, v_pages, block_table, kv_len, o=N
                                     _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
     _check(st, "powattn_decode_paged")
     return o, lse
+
+
+def backward_workspace_bytes(pattern: Pattern, batch, n_q_heads, n_kv_heads, seq_len, head_dim) -> int:
+    return lib().powattn_backward_workspace_bytes(ctypes.byref(pattern.c()), batch, n_q_heads, n_kv_heads,
+                                                  seq_len, head_dim)
+
+
+def backward(pattern: Pattern, kv_cnt, kv_idx, q, k, v, o, lse, d_o, dq=None, dk=None, dv=None, softmax_scale=0.0,
+             workspace=None, stream=None):
+    """powattn_backward.  q/o/d_o/dq: [b,Hq,N,D]; k/v/dk/dv: [b,Hkv,N,D]; lse float32 [b,Hq,N].
+    Returns (dq, dk, dv)."""
+    batch, hq, n, d = q.shape
+    hkv = k.shape[1]
+    if k.shape != (batch, hkv, n, d) or v.shape != k.shape:
+        raise ValueError("k/v shape mismatch")
+    if o.shape != q.shape or d_o.shape != q.shape or lse.shape != (batch, hq, n):
+        raise ValueError("o/d_o/lse shape mismatch")
+    if lse.dtype != torch.float32:
+        raise ValueError("lse must be float32")
+    for t in (k, v, o, d_o):
+        if t.dtype != q.dtype:
+            raise ValueError("dtype mismatch")
+    if dq is None:
+        dq = torch.empty_like(q)
+    if dk is None:
+        dk = torch.empty_like(k)
+    if dv is None:
+        dv = torch.empty_like(v)
+    if workspace is None:
+        need = backward_workspace_bytes(pattern, batch, hq, hkv, n, d)
+        if need == 0:
+            raise PowattnError(INVALID_ARG, "powattn_backward_workspace_bytes")
+        workspace = torch.empty((need,), dtype=torch.uint8, device=q.device)
+    st = lib().powattn_backward(ctypes.byref(pattern.c()), _ptr(kv_cnt), _ptr(kv_idx), kv_idx.shape[1],
+                                _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), _ptr(d_o), _ptr(dq), _ptr(dk), _ptr(dv),
+                                batch, hq, hkv, n, d, _dtype_code(q), float(softmax_scale),
+                                _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(st, "powattn_backward")
+    return dq, dk, dv
+

@@ -229,3 +229,51 @@ extern "C" int powattn_decode_paged(const powattn_pattern* pattern,
   a.block_table = d_block_table; a.table_stride = table_stride; a.n_pages = n_pages;
   return pa_launch_decode_bf16(a);
 }
+
+extern "C" size_t powattn_backward_workspace_bytes(const powattn_pattern* pattern, int32_t batch, int32_t n_q_heads,
+                                                   int32_t n_kv_heads, int64_t seq_len, int32_t head_dim) {
+  if (pa_check_pattern(pattern) != POWATTN_OK) return 0;
+  if (batch < 1 || n_q_heads < 1 || n_kv_heads < 1 || head_dim < 1 || seq_len < 1) return 0;
+  if (n_q_heads % n_kv_heads != 0) return 0;
+  return pa_backward_workspace_bytes(*pattern, batch, n_q_heads, n_kv_heads, seq_len, head_dim);
+}
+
+extern "C" int powattn_backward(const powattn_pattern* pattern,
+                                const int32_t* d_kv_cnt, const int32_t* d_kv_idx, int32_t max_k,
+                                const void* q, const void* k, const void* v, const void* o, const float* lse,
+                                const void* d_o, void* dq, void* dk, void* dv,
+                                int32_t batch, int32_t n_q_heads, int32_t n_kv_heads, int64_t seq_len,
+                                int32_t head_dim, int32_t dtype, float softmax_scale,
+                                void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int st = pa_check_pattern(pattern);
+  if (st != POWATTN_OK) return st;
+  if (!q || !k || !v || !o || !lse || !d_o || !dq || !dk || !dv || !d_kv_cnt || !d_kv_idx) return POWATTN_INVALID_ARG;
+  if (batch < 1 || n_q_heads < 1 || n_kv_heads < 1 || head_dim < 1 || seq_len < 1 || max_k < 1) return POWATTN_INVALID_ARG;
+  if (n_q_heads % n_kv_heads != 0) return POWATTN_INVALID_ARG;
+  if (!(softmax_scale == softmax_scale)) return POWATTN_INVALID_ARG;
+  if (dtype != POWATTN_BF16) return POWATTN_UNSUPPORTED;
+  if (!supported_head_dim(head_dim)) return POWATTN_UNSUPPORTED;
+  if (pattern->block != 64 && pattern->block != 128 && pattern->block != 256) return POWATTN_UNSUPPORTED;
+  if (pattern->flags & POWATTN_DENSE) return POWATTN_UNSUPPORTED;
+  const int64_t nb = powattn_num_blocks(pattern, seq_len);
+  if (nb < 0) return POWATTN_INVALID_ARG;
+  if (nb > 0x7fffffffLL) return POWATTN_UNSUPPORTED;
+  const int32_t need_k = powattn_max_k(pattern, seq_len);
+  if (need_k < 0) return POWATTN_INVALID_ARG;
+  if (max_k < need_k) return POWATTN_WORKSPACE_TOO_SMALL;      // the lists must be the pattern's own rows
+  const size_t need = pa_backward_workspace_bytes(*pattern, batch, n_q_heads, n_kv_heads, seq_len, head_dim);
+  if (!workspace || workspace_bytes < need) return POWATTN_WORKSPACE_TOO_SMALL;
+  if (((uintptr_t)workspace & 255u) != 0) return POWATTN_INVALID_ARG;
+
+  pa_backward_args a;
+  a.pat = *pattern;
+  a.kv_cnt = d_kv_cnt; a.kv_idx = d_kv_idx; a.max_k = max_k;
+  a.q = q; a.k = k; a.v = v; a.o = o; a.dout = d_o; a.lse = lse;
+  a.dq = dq; a.dk = dk; a.dv = dv;
+  a.batch = batch; a.hq = n_q_heads; a.hkv = n_kv_heads; a.nb = (int32_t)nb; a.head_dim = head_dim;
+  a.seq_len = seq_len;
+  a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)head_dim);
+  a.workspace = workspace;
+  a.stream = (hipStream_t)hip_stream;
+  return pa_launch_backward_bf16(a);
+}

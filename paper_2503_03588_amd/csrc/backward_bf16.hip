@@ -1,0 +1,585 @@
+// Gradients of Equation 1 (Section 3.1) under the block pattern of Algorithm 1, bf16 inputs, fp32 accumulation.
+// The paper trains with the sparse pattern in place (Section 4.1), which needs dQ, dK and dV of
+//   O = softmax(mask(scale Q K^T)) V.
+// With P the softmax (recomputed from the saved log-sum-exp), dP = dO V^T, Delta_i = sum_d dO_id O_id and
+// dS = P * (dP - Delta):   dQ = scale dS K,   dK = scale dS^T Q,   dV = P^T dO.
+//
+// Three kernels:
+//   delta : Delta = rowsum(dO * O), one fp32 per (batch, query head, token)
+//   dq    : a workgroup per (batch, KV head, query block, group of query-head slices) walks the row's key blocks
+//           (the lists powattn_mask_build writes), as the forward pass does; wavefront = 32 queries of one head,
+//           lane = one query.  S^T = K Q^T and dP^T = V dO^T share the K/V tiles in LDS; dQ^T += K^T dS^T.
+//   dkv   : a workgroup per (batch, KV head, key block) walks the COLUMN of the block mask: the query blocks
+//           j .. j+W-1 and j + 2^k (closed form), all of them for a sink block; wavefront = 32 keys, lane = one key.
+//           Q and dO tiles of 64 queries go through LDS; dV^T += dO^T P, dK^T += Q^T dS.  A sink block's column is
+//           as long as the sequence: it is cut into parts that add into an fp32 buffer, converted at the end.
+// Both products of a pair reuse the forward kernel's operand trick: in the transposed form the accumulator layout
+// of the first product is the B-operand layout of the second (the permutation of the contraction index inside a
+// 16-step is applied to both operands).  Tiles use the forward kernel's LDS layout (chunk-major kilobytes, padded),
+// copied asynchronously global -> LDS, two stages, one barrier per tile.  Not yet scheduled by hand.
+#include <math.h>
+#include "common.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((address_space(3))) char lds_char;
+typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
+
+constexpr int KT = 64;            // rows per staged tile
+constexpr int TILE_CAP = 2048;    // tiles per query block in the dq kernel
+constexpr int PART = 16;          // query blocks per part of a sink block's column
+constexpr float LOG2E = 1.44269504088896340736f;
+
+struct bwd_params {
+  const __bf16* q; const __bf16* k; const __bf16* v; const __bf16* o; const __bf16* dout; const float* lse;
+  __bf16* dq; __bf16* dk; __bf16* dv;
+  float* delta;          // [batch, hq, N]
+  float* dk_sink;        // [batch, hkv, sink_rows, D] fp32 sums of the sink blocks' parts
+  float* dv_sink;
+  const int32_t* kv_cnt; const int32_t* kv_idx;
+  int32_t max_k, nb, B, W, S; uint32_t flags;
+  int32_t hq, hkv, G, subs, tasks, chunks;
+  int32_t sink_blocks;   // min(S, nb) (0 when the column of no block is cut)
+  int32_t max_parts;     // parts of the longest column
+  int64_t N;
+  float scale, c2;
+};
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+__device__ __forceinline__ void async_copy16(const void* sbase, uint32_t voff, uint32_t lds_off) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_off) : "memory");
+}
+template <typename T>
+__device__ __forceinline__ const T* uniform_ptr(const T* ptr) {
+  const uint64_t u = (uint64_t)(uintptr_t)ptr;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)u), hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
+  return (const T*)(uintptr_t)(((uint64_t)hi << 32) | lo);
+}
+__device__ __forceinline__ uint32_t pack2(float x, float y) {
+  const f32x2 v = {x, y};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+// Geometry of a staged tile of 64 rows x D bf16 (the forward kernel's layout).
+template <int D>
+struct tile_geo {
+  static constexpr int ROWB = 2 * D;
+  static constexpr int CPR = D / 8;
+  static constexpr int RPI = 64 / CPR;          // rows per wavefront-wide copy instruction
+  static constexpr int IPT = KT / RPI;          // copy instructions per tile
+  static constexpr int SRB = 1024 + 16 * RPI;   // LDS distance between consecutive copy instructions' kilobytes
+  static constexpr int TILEB = IPT * SRB;
+  static constexpr int NC = D / 16;             // 16-wide steps of the head dimension
+  static constexpr int ND = D / 32;             // 32-row tiles of a transposed accumulator
+  static constexpr int K_C = 32 * RPI, K_RT = (32 / RPI) * SRB;
+  static constexpr int V_KK = (16 / RPI) * SRB, V_DT = 4 * RPI * 16, V_HI = (8 / RPI) * SRB;
+};
+
+// Copies rows row0 .. row0+63 of a row-major [rows, D] array (rows beyond `last_row` repeat it) into the LDS tile
+// at `dst`; the NWV wavefronts of the workgroup share the tile's copy instructions.
+template <int D, int NWV>
+__device__ __forceinline__ void copy_tile(const __bf16* base, int64_t row0, int64_t last_row, uint32_t dst, int wave, int lane) {
+  using G = tile_geo<D>;
+  const int cp_row = lane % G::RPI, cp_chunk = lane / G::RPI;
+  int64_t r0 = row0 < last_row ? row0 : last_row;
+  const int lim = (int)(last_row - r0);
+  const __bf16* sb = uniform_ptr(base + r0 * D);
+  for (int inst = wave; inst < G::IPT; inst += NWV) {
+    int row = G::RPI * inst + cp_row;
+    row = row < lim ? row : lim;
+    const uint32_t voff = (uint32_t)row * G::ROWB + (cp_chunk << 4);
+    async_copy16(sb, voff, __builtin_amdgcn_readfirstlane(dst + inst * G::SRB));
+  }
+}
+// A operand "rows of the tile": rows 32rt + (lane%32), elements 16c + 8(lane/32) .. +7
+template <int D>
+__device__ __forceinline__ bf16x8 row_frag(uint32_t tile, int c, int rt, int lane) {
+  using G = tile_geo<D>;
+  const int ln = lane & 31, hh = lane >> 5;
+  const uint32_t a = tile + (ln / G::RPI) * G::SRB + ((hh * G::RPI + ln % G::RPI) << 4) + c * G::K_C + rt * G::K_RT;
+  return *reinterpret_cast<const lds_bf16x8*>((uintptr_t)a);
+}
+// A operand "transposed tile": row = element 32dt + lane%32 of the head dimension, contraction over the tile's rows
+// 16kk .. 16kk+15 in the order {0..3, 8..11} + 4(lane/32), {4..7, 12..15} for the other half-wave
+template <int D>
+__device__ __forceinline__ bf16x8 tr_frag(uint32_t tile, int kk, int dt, int lane) {
+  using G = tile_geo<D>;
+  const int hh = lane >> 5;
+  const int r4 = 4 * hh + ((lane & 15) >> 2);
+  const int x = 2 * ((lane >> 4) & 1) + ((lane & 3) >> 1);
+  const uint32_t a = tile + (r4 / G::RPI) * G::SRB + ((x * G::RPI + r4 % G::RPI) << 4) + 8 * (lane & 1) + kk * G::V_KK + dt * G::V_DT;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)a);
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(a + G::V_HI));
+  return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+// B operand "rows held in registers": lane = row (lane%32), elements 16c + 8(lane/32) .. +7; zero when !ok
+template <int D>
+__device__ __forceinline__ void reg_rows(const __bf16* row, bool ok, int lane, bf16x8 (&f)[D / 16]) {
+  const int hh = lane >> 5;
+#pragma unroll
+  for (int c = 0; c < D / 16; ++c) {
+    const bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+    f[c] = ok ? *reinterpret_cast<const bf16x8*>(row + 16 * c + 8 * hh) : z;
+  }
+}
+// Element rg (0..15) of a 32x32 accumulator is row 8(rg/4) + 4(lane/32) + rg%4, column lane%32.
+__device__ __forceinline__ int acc_row(int rg, int hh) { return 8 * (rg >> 2) + 4 * hh + (rg & 3); }
+
+// ---------------------------------------------------------------------------------------------------------------
+// Delta = rowsum(dO * O)
+// ---------------------------------------------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void pa_bwd_delta_kernel(const __bf16* o, const __bf16* dout, float* delta, int64_t rows) {
+  constexpr int LPR = D / 8;                 // lanes per row
+  const int64_t row = ((int64_t)blockIdx.x * 256 + threadIdx.x) / LPR;
+  const int sub = threadIdx.x % LPR;
+  float s = 0.f;
+  if (row < rows) {
+    const bf16x8 a = *reinterpret_cast<const bf16x8*>(o + row * D + 8 * sub);
+    const bf16x8 b = *reinterpret_cast<const bf16x8*>(dout + row * D + 8 * sub);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s = fmaf((float)a[e], (float)b[e], s);
+  }
+#pragma unroll
+  for (int m = LPR / 2; m >= 1; m >>= 1) s += __shfl_xor(s, m);
+  if (row < rows && sub == 0) delta[row] = s;
+}
+
+__global__ __launch_bounds__(256) void pa_bwd_zero_kernel(float* p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0.f;
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// dQ
+// ---------------------------------------------------------------------------------------------------------------
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW) void pa_bwd_dq_kernel(bwd_params p) {
+  using G = tile_geo<D>;
+  constexpr int NC = G::NC, ND = G::ND;
+  constexpr int STAGEB = 2 * G::TILEB;           // K tile then V tile
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  __shared__ int s_tile[TILE_CAP];
+  __shared__ int s_ntiles;
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char*)smem;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int ln = lane & 31, hh = lane >> 5;
+  const int slices = p.B / 32;
+
+  // item: ((b*hkv + kvh)*nb + i)*chunks + chunk
+  int64_t L = blockIdx.x;
+  const int chunk = (int)(L % p.chunks); L /= p.chunks;
+  const int i = (int)(L % p.nb); L /= p.nb;
+  const int kvh = (int)(L % p.hkv);
+  const int b = (int)(L / p.hkv);
+
+  // ---- the row's tiles: every 64-key tile of every listed block up to the diagonal one ----
+  if (tid == 0) {
+    int n = p.kv_cnt[i];
+    if (n > p.max_k) n = p.max_k;
+    int w = 0;
+    for (int e = 0; e < n; ++e) {
+      const int j = p.kv_idx[(int64_t)i * p.max_k + e];
+      if (j < 0 || j > i) continue;
+      for (int u = 0; u < p.subs && w < TILE_CAP; ++u) s_tile[w++] = j * p.B + u * KT;
+    }
+    s_ntiles = w;
+  }
+  __syncthreads();
+  const int n_tiles = s_ntiles;
+
+  const int task = chunk * NW + wave;
+  const bool active = task < p.tasks;
+  const int g = active ? task / slices : 0, sl = active ? task % slices : 0;
+  const int h = kvh * p.G + g;
+  const int64_t tok = (int64_t)i * p.B + sl * 32 + ln;          // this lane's query
+  const bool ok = active && tok < p.N;
+  const int64_t qrow = ((int64_t)b * p.hq + h) * p.N + (ok ? tok : 0);
+
+  bf16x8 qf[NC], dof[NC];
+  reg_rows<D>(p.q + qrow * D, ok, lane, qf);
+  reg_rows<D>(p.dout + qrow * D, ok, lane, dof);
+  const float lse2 = ok ? p.lse[qrow] * LOG2E : INFINITY;        // exp2(s - inf) = 0: idle lanes contribute nothing
+  const float dl = ok ? p.delta[qrow] : 0.f;
+
+  f32x16 acc[ND];
+#pragma unroll
+  for (int dt = 0; dt < ND; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[dt][r] = 0.f;
+
+  const __bf16* kslab = p.k + ((int64_t)b * p.hkv + kvh) * p.N * D;
+  const __bf16* vslab = p.v + ((int64_t)b * p.hkv + kvh) * p.N * D;
+  auto fill = [&](int t) {
+    const int key0 = s_tile[t];
+    const uint32_t dst = lds0 + (t & 1) * STAGEB;
+    copy_tile<D, NW>(kslab, key0, p.N - 1, dst, wave, lane);
+    copy_tile<D, NW>(vslab, key0, p.N - 1, dst + G::TILEB, wave, lane);
+  };
+  if (n_tiles > 0) fill(0);
+  // the compiler's own loads above are complete before the loop; inside it only the copies are outstanding
+  for (int t = 0; t < n_tiles; ++t) {
+    wait_vmcnt<0>();
+    __syncthreads();                       // tile t has landed for everybody; everybody is done with tile t-1
+    if (t + 1 < n_tiles) fill(t + 1);
+    const int key0 = s_tile[t];
+    // tiles that start beyond this wavefront's last query are masked out entirely for it
+    if (!active || (int64_t)key0 > (int64_t)i * p.B + sl * 32 + 31) continue;
+    const uint32_t kt = lds0 + (t & 1) * STAGEB, vt = kt + G::TILEB;
+    f32x16 S[2], dP[2];
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { S[rt][r] = 0.f; dP[rt][r] = 0.f; }
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        S[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag<D>(kt, c, rt, lane), qf[c], S[rt], 0, 0, 0);
+        dP[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag<D>(vt, c, rt, lane), dof[c], dP[rt], 0, 0, 0);
+      }
+    }
+    // dS^T = P^T * (dP^T - Delta), packed to bf16 in the B-operand order of the next product
+    u32x4 ds[4];
+#pragma unroll
+    for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+      for (int r = 0; r < 16; r += 2) {
+        float x[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const int64_t key = (int64_t)key0 + 32 * rt + acc_row(r + e, hh);
+          const bool att = key <= tok && key < p.N;
+          const float pr = att ? __builtin_amdgcn_exp2f(fmaf(S[rt][r + e], p.c2, -lse2)) : 0.f;
+          x[e] = pr * (dP[rt][r + e] - dl);
+        }
+        const int rg = 16 * rt + r;
+        ds[rg >> 3][(rg & 7) >> 1] = pack2(x[0], x[1]);
+      }
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+      for (int dt = 0; dt < ND; ++dt)
+        acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag<D>(kt, kk, dt, lane), __builtin_bit_cast(bf16x8, ds[kk]), acc[dt], 0, 0, 0);
+  }
+  wait_vmcnt<0>();
+
+  // element r of tile dt is d = 32dt + 8(r/4) + 4hh + r%4 of this lane's query row: 8-byte pieces
+  if (ok) {
+    __bf16* out = p.dq + qrow * D;
+#pragma unroll
+    for (int dt = 0; dt < ND; ++dt)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const u32x2 w = {pack2(acc[dt][4 * r4] * p.scale, acc[dt][4 * r4 + 1] * p.scale),
+                         pack2(acc[dt][4 * r4 + 2] * p.scale, acc[dt][4 * r4 + 3] * p.scale)};
+        *reinterpret_cast<u32x2*>(out + 32 * dt + 8 * r4 + 4 * hh) = w;
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// dK, dV
+// ---------------------------------------------------------------------------------------------------------------
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW) void pa_bwd_dkv_kernel(bwd_params p) {
+  using G = tile_geo<D>;
+  constexpr int NC = G::NC, ND = G::ND;
+  constexpr int STAGEB = 2 * G::TILEB + 512;     // Q tile, dO tile, 64 log-sum-exps, 64 Deltas
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char*)smem;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int ln = lane & 31, hh = lane >> 5;
+  const int kvh = blockIdx.y, b = blockIdx.z;
+
+  // ---- which key block, which part of its column ----
+  int j, part;
+  if ((int)blockIdx.x < p.nb) { j = blockIdx.x; part = 0; }
+  else {
+    const int e = (int)blockIdx.x - p.nb;
+    j = e / (p.max_parts - 1);
+    part = 1 + e % (p.max_parts - 1);
+  }
+  const bool whole_column = j < p.sink_blocks;                    // a sink block: every later query block
+  const int parts = whole_column ? (p.nb - j + PART - 1) / PART : 1;
+  if (part >= parts) return;                                      // uniform over the workgroup
+  // entries of the column: query blocks j .. j+n_win-1, then j + 2^k for 2^k >= the window
+  const int weff = (p.flags & POWATTN_POWER) ? (p.W > 1 ? p.W : 1) : p.W;
+  int n_win, n_ent, first_pow = 1;
+  if (whole_column) {
+    n_win = p.nb - j - part * PART;
+    if (n_win > PART) n_win = PART;
+    n_ent = n_win;
+  } else {
+    n_win = weff < p.nb - j ? weff : p.nb - j;
+    n_ent = n_win;
+    if (p.flags & POWATTN_POWER) {
+      while (first_pow < weff) first_pow <<= 1;
+      for (int64_t pw = first_pow; j + pw < p.nb; pw <<= 1) ++n_ent;
+    }
+  }
+  auto entry = [&](int e) -> int {
+    if (whole_column) return j + part * PART + e;
+    if (e < n_win) return j + e;
+    return j + (first_pow << (e - n_win));
+  };
+
+  // ---- this lane's key: its K and V rows stay in registers as B operands ----
+  const int64_t key = (int64_t)j * p.B + 32 * wave + ln;
+  const bool kok = key < p.N;
+  const int64_t krow = ((int64_t)b * p.hkv + kvh) * p.N + (kok ? key : 0);
+  bf16x8 kf[NC], vf[NC];
+  reg_rows<D>(p.k + krow * D, kok, lane, kf);
+  reg_rows<D>(p.v + krow * D, kok, lane, vf);
+
+  f32x16 dkt[ND], dvt[ND];
+#pragma unroll
+  for (int dt = 0; dt < ND; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { dkt[dt][r] = 0.f; dvt[dt][r] = 0.f; }
+
+  // tile sequence: entry e, query head g of the group, 64-query piece u of the block
+  const int n_tiles = n_ent * p.G * p.subs;
+  auto locate = [&](int t, int& i, int& h, int64_t& q0) {
+    const int u = t % p.subs, gg = (t / p.subs) % p.G, e = t / (p.subs * p.G);
+    i = entry(e);
+    h = kvh * p.G + gg;
+    q0 = (int64_t)i * p.B + u * KT;
+  };
+  auto fill = [&](int t) {
+    int i, h; int64_t q0;
+    locate(t, i, h, q0);
+    const uint32_t dst = lds0 + (t & 1) * STAGEB;
+    const int64_t head_rows = ((int64_t)b * p.hq + h) * p.N;
+    copy_tile<D, NW>(p.q + head_rows * D, q0, p.N - 1, dst, wave, lane);
+    copy_tile<D, NW>(p.dout + head_rows * D, q0, p.N - 1, dst + G::TILEB, wave, lane);
+    if (tid < 64) {
+      const int64_t qi = q0 + tid;
+      const bool qok = qi < p.N;
+      const float l2 = qok ? p.lse[head_rows + qi] * LOG2E : INFINITY;    // rows beyond the sequence: P = 0
+      const float dd = qok ? p.delta[head_rows + qi] : 0.f;
+      float* vec = reinterpret_cast<float*>(smem + (t & 1) * STAGEB + 2 * G::TILEB);
+      vec[tid] = l2;
+      vec[64 + tid] = dd;
+    }
+  };
+  if (n_tiles > 0) fill(0);
+  for (int t = 0; t < n_tiles; ++t) {
+    wait_vmcnt<0>();
+    __syncthreads();
+    if (t + 1 < n_tiles) fill(t + 1);
+    int i, h; int64_t q0;
+    locate(t, i, h, q0);
+    const uint32_t qt = lds0 + (t & 1) * STAGEB, dot = qt + G::TILEB;
+    const float* vec = reinterpret_cast<const float*>(smem + (t & 1) * STAGEB + 2 * G::TILEB);
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const int64_t qh0 = q0 + 32 * half;                 // first query of this half
+      // causal: nothing to do when every query of the half precedes every key of the wavefront
+      if (qh0 + 31 < (int64_t)j * p.B + 32 * wave) continue;
+      if (qh0 >= p.N) continue;
+      f32x16 S, dP;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { S[r] = 0.f; dP[r] = 0.f; }
+#pragma unroll
+      for (int c = 0; c < NC; ++c) {
+        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag<D>(qt, c, half, lane), kf[c], S, 0, 0, 0);
+        dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag<D>(dot, c, half, lane), vf[c], dP, 0, 0, 0);
+      }
+      u32x4 pp[2], dsp[2];
+#pragma unroll
+      for (int r = 0; r < 16; r += 2) {
+        float x[2], y[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          const int lr = 32 * half + acc_row(r + e, hh);            // row of the tile
+          const int64_t qi = q0 + lr;
+          const bool att = kok && qi >= key;                        // rows beyond the sequence carry lse = inf
+          const float pr = att ? __builtin_amdgcn_exp2f(fmaf(S[r + e], p.c2, -vec[lr])) : 0.f;
+          x[e] = pr;
+          y[e] = pr * (dP[r + e] - vec[64 + lr]);
+        }
+        pp[r >> 3][(r & 7) >> 1] = pack2(x[0], x[1]);
+        dsp[r >> 3][(r & 7) >> 1] = pack2(y[0], y[1]);
+      }
+#pragma unroll
+      for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+        for (int dt = 0; dt < ND; ++dt) {
+          dvt[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag<D>(dot, 2 * half + k2, dt, lane), __builtin_bit_cast(bf16x8, pp[k2]), dvt[dt], 0, 0, 0);
+          dkt[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag<D>(qt, 2 * half + k2, dt, lane), __builtin_bit_cast(bf16x8, dsp[k2]), dkt[dt], 0, 0, 0);
+        }
+    }
+  }
+  wait_vmcnt<0>();
+
+  if (!kok) return;
+  if (!whole_column) {
+    __bf16* ok_ = p.dk + krow * D;
+    __bf16* ov_ = p.dv + krow * D;
+#pragma unroll
+    for (int dt = 0; dt < ND; ++dt)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const u32x2 wk = {pack2(dkt[dt][4 * r4] * p.scale, dkt[dt][4 * r4 + 1] * p.scale),
+                          pack2(dkt[dt][4 * r4 + 2] * p.scale, dkt[dt][4 * r4 + 3] * p.scale)};
+        const u32x2 wv = {pack2(dvt[dt][4 * r4], dvt[dt][4 * r4 + 1]), pack2(dvt[dt][4 * r4 + 2], dvt[dt][4 * r4 + 3])};
+        *reinterpret_cast<u32x2*>(ok_ + 32 * dt + 8 * r4 + 4 * hh) = wk;
+        *reinterpret_cast<u32x2*>(ov_ + 32 * dt + 8 * r4 + 4 * hh) = wv;
+      }
+  } else {
+    const int64_t srow = ((int64_t)b * p.hkv + kvh) * ((int64_t)p.sink_blocks * p.B) + key;   // key < sink_blocks * B
+    float* sk = p.dk_sink + srow * D;
+    float* sv = p.dv_sink + srow * D;
+#pragma unroll
+    for (int dt = 0; dt < ND; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int d = 32 * dt + acc_row(r, hh);
+        atomicAdd(sk + d, dkt[dt][r] * p.scale);
+        atomicAdd(sv + d, dvt[dt][r]);
+      }
+  }
+}
+
+// the sink blocks' fp32 sums -> bf16 rows of dK and dV
+template <int D>
+__global__ __launch_bounds__(256) void pa_bwd_sink_store_kernel(bwd_params p, int64_t total) {
+  const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;      // over [batch*hkv, sink_rows, D]
+  if (e >= total) return;
+  const int64_t sink_rows = (int64_t)p.sink_blocks * p.B;
+  const int d = (int)(e % D);
+  const int64_t key = (e / D) % sink_rows, bh = e / (D * sink_rows);
+  if (key >= p.N) return;
+  p.dk[(bh * p.N + key) * D + d] = (__bf16)p.dk_sink[e];
+  p.dv[(bh * p.N + key) * D + d] = (__bf16)p.dv_sink[e];
+}
+
+template <int D, int NW>
+int launch_dq(const bwd_params& p, int64_t items, hipStream_t stream) {
+  constexpr size_t lds = 2 * 2 * (size_t)tile_geo<D>::TILEB;
+  static bool done = false;
+  if (!done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pa_bwd_dq_kernel<D, NW>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return pa_note_hip(e);
+    done = true;
+  }
+  hipLaunchKernelGGL((pa_bwd_dq_kernel<D, NW>), dim3((uint32_t)items), dim3(64 * NW), lds, stream, p);
+  return pa_note_hip(hipGetLastError());
+}
+template <int D, int NW>
+int launch_dkv(const bwd_params& p, dim3 grid, hipStream_t stream) {
+  constexpr size_t lds = 2 * (2 * (size_t)tile_geo<D>::TILEB + 512);
+  static bool done = false;
+  if (!done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pa_bwd_dkv_kernel<D, NW>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return pa_note_hip(e);
+    done = true;
+  }
+  hipLaunchKernelGGL((pa_bwd_dkv_kernel<D, NW>), grid, dim3(64 * NW), lds, stream, p);
+  return pa_note_hip(hipGetLastError());
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+}  // namespace
+
+size_t pa_backward_workspace_bytes(const powattn_pattern& pat, int32_t batch, int32_t hq, int32_t hkv, int64_t seq_len, int32_t head_dim) {
+  const int64_t nb = (seq_len + pat.block - 1) / pat.block;
+  const int64_t sink_rows = (pat.sink < nb ? pat.sink : nb) * (int64_t)pat.block;
+  return align256((size_t)batch * hq * seq_len * sizeof(float)) +
+         2 * align256((size_t)batch * hkv * sink_rows * head_dim * sizeof(float));
+}
+
+int pa_launch_backward_bf16(const pa_backward_args& a) {
+  bwd_params p;
+  p.q = (const __bf16*)a.q; p.k = (const __bf16*)a.k; p.v = (const __bf16*)a.v; p.o = (const __bf16*)a.o;
+  p.dout = (const __bf16*)a.dout; p.lse = a.lse;
+  p.dq = (__bf16*)a.dq; p.dk = (__bf16*)a.dk; p.dv = (__bf16*)a.dv;
+  p.kv_cnt = a.kv_cnt; p.kv_idx = a.kv_idx; p.max_k = a.max_k; p.nb = a.nb;
+  p.B = a.pat.block; p.W = a.pat.window; p.S = a.pat.sink; p.flags = a.pat.flags;
+  p.hq = a.hq; p.hkv = a.hkv; p.G = a.hq / a.hkv; p.subs = p.B / KT;
+  p.N = a.seq_len; p.scale = a.scale; p.c2 = a.scale * LOG2E;
+  if ((int64_t)a.max_k * p.subs > TILE_CAP) return POWATTN_UNSUPPORTED;
+  if (a.seq_len > 0x7fffffffLL - 1024) return POWATTN_UNSUPPORTED;
+  if (p.B > 256) return POWATTN_UNSUPPORTED;                       // a wavefront per 32 keys of the block, at most 8
+  if (a.batch > 65535 || a.hkv > 65535) return POWATTN_UNSUPPORTED;
+  const int64_t tasks = (int64_t)p.G * p.B / 32;
+  if (tasks > (1 << 20)) return POWATTN_UNSUPPORTED;
+  p.tasks = (int32_t)tasks;
+  const int nwq = p.tasks > 4 ? 8 : 4;
+  p.chunks = (p.tasks + nwq - 1) / nwq;
+  p.sink_blocks = a.pat.sink < a.nb ? a.pat.sink : a.nb;
+  p.max_parts = p.sink_blocks > 0 ? (a.nb + PART - 1) / PART : 1;
+  if (p.max_parts < 2) p.max_parts = 2;                            // keeps the part arithmetic of the kernel defined
+
+  // workspace: Delta, then the sink blocks' sums
+  unsigned char* ws = (unsigned char*)a.workspace;
+  p.delta = (float*)ws;
+  ws += align256((size_t)a.batch * a.hq * a.seq_len * sizeof(float));
+  const int64_t sink_elems = (int64_t)a.batch * a.hkv * p.sink_blocks * p.B * a.head_dim;
+  p.dk_sink = (float*)ws;
+  ws += align256((size_t)sink_elems * sizeof(float));
+  p.dv_sink = (float*)ws;
+
+  const int64_t rows = (int64_t)a.batch * a.hq * a.seq_len;
+  const int lpr = a.head_dim / 8;
+  const int64_t dblocks = (rows * lpr + 255) / 256;
+  if (dblocks > 0x7fffffffLL) return POWATTN_UNSUPPORTED;
+  if (a.head_dim == 128)
+    hipLaunchKernelGGL((pa_bwd_delta_kernel<128>), dim3((uint32_t)dblocks), dim3(256), 0, a.stream, p.o, p.dout, p.delta, rows);
+  else
+    hipLaunchKernelGGL((pa_bwd_delta_kernel<64>), dim3((uint32_t)dblocks), dim3(256), 0, a.stream, p.o, p.dout, p.delta, rows);
+  int st = pa_note_hip(hipGetLastError());
+  if (st != POWATTN_OK) return st;
+  if (sink_elems > 0) {
+    const int64_t zb = (2 * (int64_t)(align256((size_t)sink_elems * sizeof(float)) / sizeof(float)) + 255) / 256;
+    hipLaunchKernelGGL(pa_bwd_zero_kernel, dim3((uint32_t)zb), dim3(256), 0, a.stream, p.dk_sink,
+                       2 * (int64_t)(align256((size_t)sink_elems * sizeof(float)) / sizeof(float)));
+    st = pa_note_hip(hipGetLastError());
+    if (st != POWATTN_OK) return st;
+  }
+
+  const int64_t items = (int64_t)a.batch * a.hkv * a.nb * p.chunks;
+  if (items > 0x7fffffffLL) return POWATTN_UNSUPPORTED;
+  if (a.head_dim == 128) st = nwq == 8 ? launch_dq<128, 8>(p, items, a.stream) : launch_dq<128, 4>(p, items, a.stream);
+  else st = nwq == 8 ? launch_dq<64, 8>(p, items, a.stream) : launch_dq<64, 4>(p, items, a.stream);
+  if (st != POWATTN_OK) return st;
+
+  const int64_t gx = (int64_t)a.nb + (int64_t)p.sink_blocks * (p.max_parts - 1);
+  if (gx > 0x7fffffffLL) return POWATTN_UNSUPPORTED;
+  const dim3 grid((uint32_t)gx, (uint32_t)a.hkv, (uint32_t)a.batch);
+  const int nwk = p.B / 32;
+  if (a.head_dim == 128)
+    st = nwk == 2 ? launch_dkv<128, 2>(p, grid, a.stream) : nwk == 4 ? launch_dkv<128, 4>(p, grid, a.stream) : launch_dkv<128, 8>(p, grid, a.stream);
+  else
+    st = nwk == 2 ? launch_dkv<64, 2>(p, grid, a.stream) : nwk == 4 ? launch_dkv<64, 4>(p, grid, a.stream) : launch_dkv<64, 8>(p, grid, a.stream);
+  if (st != POWATTN_OK) return st;
+
+  if (sink_elems > 0) {
+    const int64_t sb = (sink_elems + 255) / 256;
+    if (a.head_dim == 128)
+      hipLaunchKernelGGL((pa_bwd_sink_store_kernel<128>), dim3((uint32_t)sb), dim3(256), 0, a.stream, p, sink_elems);
+    else
+      hipLaunchKernelGGL((pa_bwd_sink_store_kernel<64>), dim3((uint32_t)sb), dim3(256), 0, a.stream, p, sink_elems);
+    st = pa_note_hip(hipGetLastError());
+  }
+  return st;
+}

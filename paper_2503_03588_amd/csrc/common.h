@@ -48,4 +48,18 @@ struct pa_decode_args {
   int64_t n_pages;
 };
 int pa_launch_decode_bf16(const pa_decode_args& a);
+
+struct pa_backward_args {
+  powattn_pattern pat;
+  const int32_t* kv_cnt; const int32_t* kv_idx; int32_t max_k;
+  const void* q; const void* k; const void* v; const void* o; const void* dout; const float* lse;
+  void* dq; void* dk; void* dv;
+  int32_t batch, hq, hkv, nb, head_dim;
+  int64_t seq_len;
+  float scale;
+  void* workspace;
+  hipStream_t stream;
+};
+int pa_launch_backward_bf16(const pa_backward_args& a);
+size_t pa_backward_workspace_bytes(const powattn_pattern& pat, int32_t batch, int32_t hq, int32_t hkv, int64_t seq_len, int32_t head_dim);
 int32_t pa_decode_splits(const powattn_pattern* pat, int32_t batch, int32_t hkv, int64_t capacity);

@@ -188,6 +188,37 @@ def test_decode_paged_argument_errors(L):
     assert _paged(L, ws=FAKE + 8) == pa.INVALID_ARG
 
 
+def _backward(L, pat=None, cnt=FAKE, idx=FAKE, max_k=13, q=FAKE, k=FAKE, v=FAKE, o=FAKE, lse=FAKE, do=FAKE,
+              dq=FAKE, dk=FAKE, dv=FAKE, batch=1, hq=4, hkv=2, n=4096, d=128, dtype=pa.BF16, scale=0.0,
+              ws=FAKE, ws_bytes=None):
+    p = pat or pa.Pattern(64, 4, 1)
+    cp = p.c()
+    if ws_bytes is None:
+        ws_bytes = L.powattn_backward_workspace_bytes(ctypes.byref(cp), batch, hq, hkv, n, d)
+    return L.powattn_backward(ctypes.byref(cp), cnt, idx, max_k, q, k, v, o, lse, do, dq, dk, dv, batch, hq, hkv,
+                              n, d, dtype, scale, ws, ws_bytes, None)
+
+
+def test_backward_argument_errors(L):
+    for name in ("cnt", "idx", "q", "k", "v", "o", "lse", "do", "dq", "dk", "dv"):
+        assert _backward(L, **{name: None}) == pa.INVALID_ARG, name
+    assert _backward(L, hq=6, hkv=4) == pa.INVALID_ARG
+    assert _backward(L, n=0) == pa.INVALID_ARG
+    assert _backward(L, scale=float("nan")) == pa.INVALID_ARG
+    assert _backward(L, max_k=5) == pa.WORKSPACE_TOO_SMALL              # shorter than the pattern's rows
+    assert _backward(L, dtype=pa.F32) == pa.UNSUPPORTED
+    assert _backward(L, d=96) == pa.UNSUPPORTED
+    assert _backward(L, pat=pa.Pattern(192, 4, 1)) == pa.UNSUPPORTED
+    assert _backward(L, pat=pa.Pattern(64, 1, 0, flags=pa.DENSE)) == pa.UNSUPPORTED
+    assert _backward(L, ws=None) == pa.WORKSPACE_TOO_SMALL
+    assert _backward(L, ws_bytes=64) == pa.WORKSPACE_TOO_SMALL
+    assert _backward(L, ws=FAKE + 8) == pa.INVALID_ARG
+    cp = pa.Pattern(64, 4, 1).c()
+    n = L.powattn_backward_workspace_bytes(ctypes.byref(cp), 1, 32, 8, 131072, 128)
+    assert n >= 32 * 131072 * 4 + 2 * 8 * 64 * 128 * 4 and n % 256 == 0
+    assert L.powattn_backward_workspace_bytes(ctypes.byref(cp), 0, 32, 8, 131072, 128) == 0
+
+
 def test_decode_workspace_size(L):
     pat = pa.Pattern(64, 4, 1)
     n = pa.decode_workspace_bytes(pat, 16, 32, 8, 128, 65536)
