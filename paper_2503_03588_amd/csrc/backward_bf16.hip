@@ -5,7 +5,7 @@
 // dS = P * (dP - Delta):   dQ = scale dS K,   dK = scale dS^T Q,   dV = P^T dO.
 //
 // Three kernels:
-//   delta : Delta = rowsum(dO * O), one fp32 per (batch, query head, token)
+//   delta : Delta = rowsum(dO * O), one fp32 per (batch, query head, token), and the log-sum-exp in base 2
 //   dq    : a workgroup per (batch, KV head, query block, group of query-head slices) walks the row's key blocks
 //           (the lists powattn_mask_build writes), as the forward pass does; wavefront = 32 queries of one head,
 //           lane = one query.  S^T = K Q^T and dP^T = V dO^T share the K/V tiles in LDS; dQ^T += K^T dS^T.
@@ -38,12 +38,15 @@ typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
 constexpr int KT = 64;            // rows per staged tile
 constexpr int TILE_CAP = 2048;    // tiles per query block in the dq kernel
 constexpr int PART = 16;          // query blocks per part of a sink block's column
+constexpr int NSTG = 2;           // LDS stages of the tile stream: copies run NSTG-1 tiles ahead of the products (3 was
+                                  // slower: the extra LDS halves the workgroups per compute unit at block 64)
 constexpr float LOG2E = 1.44269504088896340736f;
 
 struct bwd_params {
   const __bf16* q; const __bf16* k; const __bf16* v; const __bf16* o; const __bf16* dout; const float* lse;
   __bf16* dq; __bf16* dk; __bf16* dv;
   float* delta;          // [batch, hq, N]
+  float* lse2;           // [batch, hq, N]: the log-sum-exp in base-2 units (lse * log2 e)
   float* dk_sink;        // [batch, hkv, sink_rows, D] fp32 sums of the sink blocks' parts
   float* dv_sink;
   const int32_t* kv_cnt; const int32_t* kv_idx;
@@ -61,6 +64,10 @@ __device__ __forceinline__ void wait_vmcnt() {
 }
 __device__ __forceinline__ void async_copy16(const void* sbase, uint32_t voff, uint32_t lds_off) {
   asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_off) : "memory");
+}
+// one dword per lane: lane l's value lands at lds_off + 4*l
+__device__ __forceinline__ void async_copy4(const void* addr, uint32_t lds_off) {
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" ::"v"(addr), "s"(lds_off) : "memory");
 }
 template <typename T>
 __device__ __forceinline__ const T* uniform_ptr(const T* ptr) {
@@ -142,7 +149,8 @@ __device__ __forceinline__ int acc_row(int rg, int hh) { return 8 * (rg >> 2) + 
 // Delta = rowsum(dO * O)
 // ---------------------------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(256) void pa_bwd_delta_kernel(const __bf16* o, const __bf16* dout, float* delta, int64_t rows) {
+__global__ __launch_bounds__(256) void pa_bwd_delta_kernel(const __bf16* o, const __bf16* dout, const float* lse, float* delta,
+                                                           float* lse2, int64_t rows) {
   constexpr int LPR = D / 8;                 // lanes per row
   const int64_t row = ((int64_t)blockIdx.x * 256 + threadIdx.x) / LPR;
   const int sub = threadIdx.x % LPR;
@@ -155,7 +163,10 @@ __global__ __launch_bounds__(256) void pa_bwd_delta_kernel(const __bf16* o, cons
   }
 #pragma unroll
   for (int m = LPR / 2; m >= 1; m >>= 1) s += __shfl_xor(s, m);
-  if (row < rows && sub == 0) delta[row] = s;
+  if (row < rows && sub == 0) {
+    delta[row] = s;
+    lse2[row] = lse[row] * LOG2E;
+  }
 }
 
 __global__ __launch_bounds__(256) void pa_bwd_zero_kernel(float* p, int64_t n) {
@@ -214,7 +225,7 @@ __global__ __launch_bounds__(64 * NW) void pa_bwd_dq_kernel(bwd_params p) {
   bf16x8 qf[NC], dof[NC];
   reg_rows<D>(p.q + qrow * D, ok, lane, qf);
   reg_rows<D>(p.dout + qrow * D, ok, lane, dof);
-  const float lse2 = ok ? p.lse[qrow] * LOG2E : INFINITY;        // exp2(s - inf) = 0: idle lanes contribute nothing
+  const float lse2 = ok ? p.lse2[qrow] : INFINITY;               // exp2(s - inf) = 0: idle lanes contribute nothing
   const float dl = ok ? p.delta[qrow] : 0.f;
 
   f32x16 acc[ND];
@@ -225,22 +236,26 @@ __global__ __launch_bounds__(64 * NW) void pa_bwd_dq_kernel(bwd_params p) {
 
   const __bf16* kslab = p.k + ((int64_t)b * p.hkv + kvh) * p.N * D;
   const __bf16* vslab = p.v + ((int64_t)b * p.hkv + kvh) * p.N * D;
+  static_assert(G::IPT % NW == 0, "tile copies must divide over the wavefronts");
+  constexpr int CPF = 2 * G::IPT / NW;     // copies per wavefront and fill (K and V)
   auto fill = [&](int t) {
     const int key0 = s_tile[t];
-    const uint32_t dst = lds0 + (t & 1) * STAGEB;
+    const uint32_t dst = lds0 + (t % NSTG) * STAGEB;
     copy_tile<D, NW>(kslab, key0, p.N - 1, dst, wave, lane);
     copy_tile<D, NW>(vslab, key0, p.N - 1, dst + G::TILEB, wave, lane);
   };
-  if (n_tiles > 0) fill(0);
-  // the compiler's own loads above are complete before the loop; inside it only the copies are outstanding
+  for (int s0 = 0; s0 < NSTG - 1; ++s0)
+    if (s0 < n_tiles) fill(s0);
+  // Tile t has landed when only the fills of tiles t+1 .. t+NSTG-2 are outstanding (the counter retires in
+  // order; the loads of Q, dO above are older still).  Near the end, where fewer fills follow, wait for all.
   for (int t = 0; t < n_tiles; ++t) {
-    wait_vmcnt<0>();
+    if (t + NSTG - 1 <= n_tiles) wait_vmcnt<(NSTG - 2) * CPF>(); else wait_vmcnt<0>();
     __syncthreads();                       // tile t has landed for everybody; everybody is done with tile t-1
-    if (t + 1 < n_tiles) fill(t + 1);
+    if (t + NSTG - 1 < n_tiles) fill(t + NSTG - 1);      // into the stage tile t-1 has just left
     const int key0 = s_tile[t];
     // tiles that start beyond this wavefront's last query are masked out entirely for it
     if (!active || (int64_t)key0 > (int64_t)i * p.B + sl * 32 + 31) continue;
-    const uint32_t kt = lds0 + (t & 1) * STAGEB, vt = kt + G::TILEB;
+    const uint32_t kt = lds0 + (t % NSTG) * STAGEB, vt = kt + G::TILEB;
     f32x16 S[2], dP[2];
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt) {
@@ -364,29 +379,37 @@ __global__ __launch_bounds__(64 * NW) void pa_bwd_dkv_kernel(bwd_params p) {
   auto fill = [&](int t) {
     int i, h; int64_t q0;
     locate(t, i, h, q0);
-    const uint32_t dst = lds0 + (t & 1) * STAGEB;
+    const uint32_t dst = lds0 + (t % NSTG) * STAGEB;
     const int64_t head_rows = ((int64_t)b * p.hq + h) * p.N;
     copy_tile<D, NW>(p.q + head_rows * D, q0, p.N - 1, dst, wave, lane);
     copy_tile<D, NW>(p.dout + head_rows * D, q0, p.N - 1, dst + G::TILEB, wave, lane);
-    if (tid < 64) {
-      const int64_t qi = q0 + tid;
-      const bool qok = qi < p.N;
-      const float l2 = qok ? p.lse[head_rows + qi] * LOG2E : INFINITY;    // rows beyond the sequence: P = 0
-      const float dd = qok ? p.delta[head_rows + qi] : 0.f;
-      float* vec = reinterpret_cast<float*>(smem + (t & 1) * STAGEB + 2 * G::TILEB);
-      vec[tid] = l2;
-      vec[64 + tid] = dd;
+    if (wave == 0) {
+      // the tile's 64 log-sum-exps and Deltas, copied asynchronously like the tiles (a load through registers
+      // would make this wavefront wait for memory in every iteration); rows beyond the sequence repeat the last
+      // one and are masked where they are used
+      int64_t qi = q0 + lane;
+      qi = qi < p.N ? qi : p.N - 1;
+      const uint32_t vdst = __builtin_amdgcn_readfirstlane(dst + 2 * G::TILEB);
+      async_copy4(p.lse2 + head_rows + qi, vdst);
+      async_copy4(p.delta + head_rows + qi, vdst + 256);
     }
   };
-  if (n_tiles > 0) fill(0);
+  static_assert(G::IPT % NW == 0, "tile copies must divide over the wavefronts");
+  constexpr int CPF = 2 * G::IPT / NW;     // copies per wavefront and fill (Q and dO); the first wavefront adds two
+  for (int s0 = 0; s0 < NSTG - 1; ++s0)
+    if (s0 < n_tiles) fill(s0);
   for (int t = 0; t < n_tiles; ++t) {
-    wait_vmcnt<0>();
+    if (t + NSTG - 1 <= n_tiles) {
+      if (wave == 0) wait_vmcnt<(NSTG - 2) * (CPF + 2)>(); else wait_vmcnt<(NSTG - 2) * CPF>();
+    } else {
+      wait_vmcnt<0>();
+    }
     __syncthreads();
-    if (t + 1 < n_tiles) fill(t + 1);
+    if (t + NSTG - 1 < n_tiles) fill(t + NSTG - 1);
     int i, h; int64_t q0;
     locate(t, i, h, q0);
-    const uint32_t qt = lds0 + (t & 1) * STAGEB, dot = qt + G::TILEB;
-    const float* vec = reinterpret_cast<const float*>(smem + (t & 1) * STAGEB + 2 * G::TILEB);
+    const uint32_t qt = lds0 + (t % NSTG) * STAGEB, dot = qt + G::TILEB;
+    const float* vec = reinterpret_cast<const float*>(smem + (t % NSTG) * STAGEB + 2 * G::TILEB);
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
       const int64_t qh0 = q0 + 32 * half;                 // first query of this half
@@ -409,7 +432,7 @@ __global__ __launch_bounds__(64 * NW) void pa_bwd_dkv_kernel(bwd_params p) {
         for (int e = 0; e < 2; ++e) {
           const int lr = 32 * half + acc_row(r + e, hh);            // row of the tile
           const int64_t qi = q0 + lr;
-          const bool att = kok && qi >= key;                        // rows beyond the sequence carry lse = inf
+          const bool att = kok && qi >= key && qi < p.N;
           const float pr = att ? __builtin_amdgcn_exp2f(fmaf(S[r + e], p.c2, -vec[lr])) : 0.f;
           x[e] = pr;
           y[e] = pr * (dP[r + e] - vec[64 + lr]);
@@ -472,7 +495,7 @@ __global__ __launch_bounds__(256) void pa_bwd_sink_store_kernel(bwd_params p, in
 
 template <int D, int NW>
 int launch_dq(const bwd_params& p, int64_t items, hipStream_t stream) {
-  constexpr size_t lds = 2 * 2 * (size_t)tile_geo<D>::TILEB;
+  constexpr size_t lds = NSTG * 2 * (size_t)tile_geo<D>::TILEB;
   static bool done = false;
   if (!done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pa_bwd_dq_kernel<D, NW>),
@@ -485,7 +508,7 @@ int launch_dq(const bwd_params& p, int64_t items, hipStream_t stream) {
 }
 template <int D, int NW>
 int launch_dkv(const bwd_params& p, dim3 grid, hipStream_t stream) {
-  constexpr size_t lds = 2 * (2 * (size_t)tile_geo<D>::TILEB + 512);
+  constexpr size_t lds = NSTG * (2 * (size_t)tile_geo<D>::TILEB + 512);
   static bool done = false;
   if (!done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pa_bwd_dkv_kernel<D, NW>),
@@ -504,7 +527,7 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 size_t pa_backward_workspace_bytes(const powattn_pattern& pat, int32_t batch, int32_t hq, int32_t hkv, int64_t seq_len, int32_t head_dim) {
   const int64_t nb = (seq_len + pat.block - 1) / pat.block;
   const int64_t sink_rows = (pat.sink < nb ? pat.sink : nb) * (int64_t)pat.block;
-  return align256((size_t)batch * hq * seq_len * sizeof(float)) +
+  return 2 * align256((size_t)batch * hq * seq_len * sizeof(float)) +
          2 * align256((size_t)batch * hkv * sink_rows * head_dim * sizeof(float));
 }
 
@@ -530,9 +553,11 @@ int pa_launch_backward_bf16(const pa_backward_args& a) {
   p.max_parts = p.sink_blocks > 0 ? (a.nb + PART - 1) / PART : 1;
   if (p.max_parts < 2) p.max_parts = 2;                            // keeps the part arithmetic of the kernel defined
 
-  // workspace: Delta, then the sink blocks' sums
+  // workspace: Delta, the log-sum-exp in base 2, then the sink blocks' sums
   unsigned char* ws = (unsigned char*)a.workspace;
   p.delta = (float*)ws;
+  ws += align256((size_t)a.batch * a.hq * a.seq_len * sizeof(float));
+  p.lse2 = (float*)ws;
   ws += align256((size_t)a.batch * a.hq * a.seq_len * sizeof(float));
   const int64_t sink_elems = (int64_t)a.batch * a.hkv * p.sink_blocks * p.B * a.head_dim;
   p.dk_sink = (float*)ws;
@@ -544,9 +569,9 @@ int pa_launch_backward_bf16(const pa_backward_args& a) {
   const int64_t dblocks = (rows * lpr + 255) / 256;
   if (dblocks > 0x7fffffffLL) return POWATTN_UNSUPPORTED;
   if (a.head_dim == 128)
-    hipLaunchKernelGGL((pa_bwd_delta_kernel<128>), dim3((uint32_t)dblocks), dim3(256), 0, a.stream, p.o, p.dout, p.delta, rows);
+    hipLaunchKernelGGL((pa_bwd_delta_kernel<128>), dim3((uint32_t)dblocks), dim3(256), 0, a.stream, p.o, p.dout, p.lse, p.delta, p.lse2, rows);
   else
-    hipLaunchKernelGGL((pa_bwd_delta_kernel<64>), dim3((uint32_t)dblocks), dim3(256), 0, a.stream, p.o, p.dout, p.delta, rows);
+    hipLaunchKernelGGL((pa_bwd_delta_kernel<64>), dim3((uint32_t)dblocks), dim3(256), 0, a.stream, p.o, p.dout, p.lse, p.delta, p.lse2, rows);
   int st = pa_note_hip(hipGetLastError());
   if (st != POWATTN_OK) return st;
   if (sink_elems > 0) {
