@@ -18,6 +18,7 @@
 // 16-step is applied to both operands).  Tiles use the forward kernel's LDS layout (chunk-major kilobytes, padded),
 // copied asynchronously global -> LDS, two stages, one barrier per tile.  Not yet scheduled by hand.
 #include <math.h>
+#include <type_traits>
 #include "common.h"
 
 namespace {
@@ -227,6 +228,7 @@ __global__ __launch_bounds__(64 * NW) void pa_bwd_dq_kernel(bwd_params p) {
   reg_rows<D>(p.dout + qrow * D, ok, lane, dof);
   const float lse2 = ok ? p.lse2[qrow] : INFINITY;               // exp2(s - inf) = 0: idle lanes contribute nothing
   const float dl = ok ? p.delta[qrow] : 0.f;
+  const int tok32 = (int)tok, n32 = (int)p.N;                    // positions fit 32 bits (checked by the host)
 
   f32x16 acc[ND];
 #pragma unroll
@@ -269,21 +271,30 @@ __global__ __launch_bounds__(64 * NW) void pa_bwd_dq_kernel(bwd_params p) {
     }
     // dS^T = P^T * (dP^T - Delta), packed to bf16 in the B-operand order of the next product
     u32x4 ds[4];
+    // Only tiles that reach the diagonal or the end of the sequence need the mask (wavefront-uniform test); the
+    // others skip the compares and selects.  Idle lanes (query beyond the sequence) carry lse = inf: P = 0.
+    auto elements = [&](auto masked) {
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt)
+      for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
-      for (int r = 0; r < 16; r += 2) {
-        float x[2];
+        for (int r = 0; r < 16; r += 2) {
+          float x[2];
 #pragma unroll
-        for (int e = 0; e < 2; ++e) {
-          const int64_t key = (int64_t)key0 + 32 * rt + acc_row(r + e, hh);
-          const bool att = key <= tok && key < p.N;
-          const float pr = att ? __builtin_amdgcn_exp2f(fmaf(S[rt][r + e], p.c2, -lse2)) : 0.f;
-          x[e] = pr * (dP[rt][r + e] - dl);
+          for (int e = 0; e < 2; ++e) {
+            // computed for every element and selected afterwards: a conditional exponential becomes a branch
+            const float pr = __builtin_amdgcn_exp2f(fmaf(S[rt][r + e], p.c2, -lse2));
+            x[e] = pr * (dP[rt][r + e] - dl);
+            if (decltype(masked)::value) {
+              const int key = key0 + 32 * rt + acc_row(r + e, hh);
+              x[e] = (key <= tok32 && key < n32) ? x[e] : 0.f;
+            }
+          }
+          const int rg = 16 * rt + r;
+          ds[rg >> 3][(rg & 7) >> 1] = pack2(x[0], x[1]);
         }
-        const int rg = 16 * rt + r;
-        ds[rg >> 3][(rg & 7) >> 1] = pack2(x[0], x[1]);
-      }
+    };
+    if ((int64_t)key0 + KT - 1 > (int64_t)i * p.B + sl * 32 || (int64_t)key0 + KT > p.N) elements(std::true_type{});
+    else elements(std::false_type{});
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk)
 #pragma unroll
@@ -357,6 +368,7 @@ __global__ __launch_bounds__(64 * NW) void pa_bwd_dkv_kernel(bwd_params p) {
   // ---- this lane's key: its K and V rows stay in registers as B operands ----
   const int64_t key = (int64_t)j * p.B + 32 * wave + ln;
   const bool kok = key < p.N;
+  const int key32 = (int)key, n32 = (int)p.N;          // positions fit 32 bits (checked by the host)
   const int64_t krow = ((int64_t)b * p.hkv + kvh) * p.N + (kok ? key : 0);
   bf16x8 kf[NC], vf[NC];
   reg_rows<D>(p.k + krow * D, kok, lane, kf);
@@ -412,10 +424,8 @@ __global__ __launch_bounds__(64 * NW) void pa_bwd_dkv_kernel(bwd_params p) {
     const float* vec = reinterpret_cast<const float*>(smem + (t % NSTG) * STAGEB + 2 * G::TILEB);
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
-      const int64_t qh0 = q0 + 32 * half;                 // first query of this half
-      // causal: nothing to do when every query of the half precedes every key of the wavefront
-      if (qh0 + 31 < (int64_t)j * p.B + 32 * wave) continue;
-      if (qh0 >= p.N) continue;
+      // (no shortcut for halves that the causal mask or the end of the sequence empties: the mask below zeroes
+      // them, and a branch around the products makes the compiler copy the 128 accumulator registers)
       f32x16 S, dP;
 #pragma unroll
       for (int r = 0; r < 16; ++r) { S[r] = 0.f; dP[r] = 0.f; }
@@ -425,21 +435,36 @@ __global__ __launch_bounds__(64 * NW) void pa_bwd_dkv_kernel(bwd_params p) {
         dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag<D>(dot, c, half, lane), vf[c], dP, 0, 0, 0);
       }
       u32x4 pp[2], dsp[2];
+      auto elements = [&](auto masked) {
 #pragma unroll
-      for (int r = 0; r < 16; r += 2) {
-        float x[2], y[2];
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const int lr0 = 32 * half + 8 * r4 + 4 * hh;                // rows lr0 .. lr0+3 of the tile
+          const f32x4 l4 = *reinterpret_cast<const f32x4*>(vec + lr0);
+          const f32x4 d4 = *reinterpret_cast<const f32x4*>(vec + 64 + lr0);
+          float x[4], y[4];
 #pragma unroll
-        for (int e = 0; e < 2; ++e) {
-          const int lr = 32 * half + acc_row(r + e, hh);            // row of the tile
-          const int64_t qi = q0 + lr;
-          const bool att = kok && qi >= key && qi < p.N;
-          const float pr = att ? __builtin_amdgcn_exp2f(fmaf(S[r + e], p.c2, -vec[lr])) : 0.f;
-          x[e] = pr;
-          y[e] = pr * (dP[r + e] - vec[64 + lr]);
+          for (int e = 0; e < 4; ++e) {
+            // computed for every element and selected afterwards: a conditional exponential becomes a branch
+            const float pr = __builtin_amdgcn_exp2f(fmaf(S[4 * r4 + e], p.c2, -l4[e]));
+            x[e] = pr;
+            y[e] = pr * (dP[4 * r4 + e] - d4[e]);
+            if (decltype(masked)::value) {
+              const int qi = (int)q0 + lr0 + e;
+              const bool att = kok && qi >= key32 && qi < n32;
+              x[e] = att ? x[e] : 0.f;
+              y[e] = att ? y[e] : 0.f;
+            }
+          }
+          const int r = 4 * r4;
+          pp[r >> 3][(r & 7) >> 1] = pack2(x[0], x[1]);
+          pp[r >> 3][((r & 7) >> 1) + 1] = pack2(x[2], x[3]);
+          dsp[r >> 3][(r & 7) >> 1] = pack2(y[0], y[1]);
+          dsp[r >> 3][((r & 7) >> 1) + 1] = pack2(y[2], y[3]);
         }
-        pp[r >> 3][(r & 7) >> 1] = pack2(x[0], x[1]);
-        dsp[r >> 3][(r & 7) >> 1] = pack2(y[0], y[1]);
-      }
+      };
+      // the mask matters on the diagonal block and where queries or keys run past the sequence (uniform test)
+      if (i == j || q0 + KT > p.N || ((int64_t)j + 1) * p.B > p.N) elements(std::true_type{});
+      else elements(std::false_type{});
 #pragma unroll
       for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
