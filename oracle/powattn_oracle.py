@@ -294,6 +294,51 @@ def attention_backward(q, k, v, do, pat: Pattern, scale=None):
     return dq, dk, dv
 
 
+def backward_sample(q, k, v, do, rows, keys, pat: Pattern, scale=None):
+    """The same gradients for a sample only, for sequences too long for the dense N x N form:
+    dq at the query positions `rows`, dk and dv at the key positions `keys`.
+
+    dq_i needs row i of P and dP only.  dk_j and dv_j sum over the queries i that attend j; for each of them
+    p_ij = exp(s_ij - lse_i) with lse_i from `attention_rows` and Delta_i = sum_d do_id o_id.
+    Returns dq [batch, Hq, len(rows), D], dk, dv [batch, Hkv, len(keys), D].
+    """
+    q, k, v, do = widen(q), widen(k), widen(v), widen(do)
+    batch, hq, n, d = q.shape
+    hkv = k.shape[1]
+    g = hq // hkv
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    rows = np.asarray(rows, dtype=np.int64)
+    keys = np.asarray(keys, dtype=np.int64)
+    dq = np.zeros((batch, hq, rows.size, d))
+    dk = np.zeros((batch, hkv, keys.size, d))
+    dv = np.zeros((batch, hkv, keys.size, d))
+    allowed_rows = token_mask_rows(rows, n, pat)
+    # every query that attends at least one sampled key
+    allq = np.arange(n, dtype=np.int64)
+    att_qk = attended(allq[:, None], keys[None, :], pat)            # [N, len(keys)]
+    qs = np.nonzero(att_qk.any(axis=1))[0]
+    att_qk = att_qk[qs]
+    for b in range(batch):
+        for h in range(hq):
+            kh, vh = k[b, h // g], v[b, h // g]
+            s = np.where(allowed_rows, scale * (q[b, h, rows] @ kh.T), -np.inf)
+            p = np.exp(s - s.max(axis=1, keepdims=True))
+            p /= p.sum(axis=1, keepdims=True)
+            dp = do[b, h, rows] @ vh.T
+            ds = p * (dp - (p * dp).sum(axis=1, keepdims=True))
+            dq[b, h] = scale * (ds @ kh)
+            if keys.size:
+                o_q, lse_q = attention_rows(q[b:b + 1, h:h + 1], kh[None, None], vh[None, None], qs, pat, scale)
+                delta = (do[b, h, qs] * o_q[0, 0]).sum(axis=1, keepdims=True)
+                sk = scale * (q[b, h, qs] @ kh[keys].T)
+                pk = np.where(att_qk, np.exp(sk - lse_q[0, 0][:, None]), 0.0)
+                dsk = pk * (do[b, h, qs] @ vh[keys].T - delta)
+                dk[b, h // g] += scale * (dsk.T @ q[b, h, qs])
+                dv[b, h // g] += pk.T @ do[b, h, qs]
+    return dq, dk, dv
+
+
 def column_lists(seq_len: int, pat: Pattern):
     """For every key block j, the query blocks that attend it, ascending (the columns of the block mask)."""
     bm = block_mask(seq_len, pat)

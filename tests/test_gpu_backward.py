@@ -75,3 +75,34 @@ def test_rows_outside_the_sink_blocks_are_reproducible():
     assert torch.equal(a[1][:, :, 64:], b[1][:, :, 64:]) and torch.equal(a[2][:, :, 64:], b[2][:, :, 64:])
     assert (a[1][:, :, :64].float() - b[1][:, :, :64].float()).abs().max().item() <= 1e-2
 
+
+
+def test_prefill_configuration_size_on_sampled_rows_and_keys():
+    # configuration 2 at its full size (batch 1, 32/8 heads, N = 32768, block 64, W = 4): the dense oracle does not
+    # fit, so sampled query rows (dQ) and sampled keys outside the sink block (dK, dV) of two KV heads are checked
+    # against the oracle's sampled form
+    pat = pa.Pattern(64, 4, 1)
+    hq, hkv, n, d = 32, 8, 32768, 128
+    q, k, v = synth.qkv(1, hq, hkv, n, d, "bf16", seed=61)
+    do = synth.gaussian((1, hq, n, d), "bf16", 62)
+    cnt, idx, _ = pa.mask_build(pat, n)
+    qd, kd, vd, dod = q.cuda(), k.cuda(), v.cuda(), do.cuda()
+    o, lse = pa.prefill(pat, cnt, idx, qd, kd, vd)
+    dq, dk, dv = pa.backward(pat, cnt, idx, qd, kd, vd, o, lse, dod)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(63)
+    rows = np.unique(np.concatenate([[0, 63, 64, n - 1], rng.integers(0, n, 20)]))
+    keys = np.unique(np.concatenate([[64, n - 1, n - 64], 64 * rng.integers(1, n // 64, 2)[:, None].repeat(3, 1).ravel()
+                                     + rng.integers(0, 64, 6)]))
+    opat = oracle_pattern(pat)
+    for kvh in (0, 7):
+        hs = slice(4 * kvh, 4 * kvh + 4)
+        rq, rk, rv = orc.backward_sample(synth.to_numpy_storage(q[:, hs]), synth.to_numpy_storage(k[:, kvh:kvh + 1]),
+                                         synth.to_numpy_storage(v[:, kvh:kvh + 1]), synth.to_numpy_storage(do[:, hs]),
+                                         rows, keys, opat)
+        got = (dq[:, hs][:, :, rows].double().cpu().numpy(), dk[:, kvh:kvh + 1][:, :, keys].double().cpu().numpy(),
+               dv[:, kvh:kvh + 1][:, :, keys].double().cpu().numpy())
+        for name, g, ref in zip(("dq", "dk", "dv"), got, (rq, rk, rv)):
+            err, bar = np.abs(g - ref).max(), TOL_G * max(1.0, np.abs(ref).max())
+            print(f"  kv head {kvh} {name}: max abs err {err:.3e} (largest entry {np.abs(ref).max():.3f})", flush=True)
+            assert err <= bar, (kvh, name, err, bar)

@@ -137,3 +137,18 @@ def test_planted_mistakes_in_the_backward_are_caught(monkeypatch):
     assert not fd_check((dq / 0.5, dk, dv))                  # dropped scale
     assert not fd_check((dq, dk.copy()[:, :, ::-1], dv))     # transposed / reversed operand
     assert not fd_check((dq, dk, dv * (1 + 1e-3)))           # slightly wrong dV
+
+
+def test_sampled_form_equals_the_dense_form():
+    batch, hq, hkv, n, d = 2, 4, 2, 150, 8
+    q, k, v = _rand((batch, hq, n, d), 24), _rand((batch, hkv, n, d), 25), _rand((batch, hkv, n, d), 26)
+    do = _rand((batch, hq, n, d), 27)
+    for pat in (Pattern(8, 2, 1), Pattern(16, 3, 0), Pattern(8, 2, 2, power=False)):
+        dq, dk, dv = orc.attention_backward(q, k, v, do, pat, 0.3)
+        rows = np.array([0, 7, 8, 64, 100, 149])
+        keys = np.array([0, 3, 8, 15, 16, 77, 148, 149])
+        sq, sk, sv = orc.backward_sample(q, k, v, do, rows, keys, pat, 0.3)
+        assert np.abs(sq - dq[:, :, rows]).max() < 1e-12
+        assert np.abs(sk - dk[:, :, keys]).max() < 1e-12
+        assert np.abs(sv - dv[:, :, keys]).max() < 1e-12
+
