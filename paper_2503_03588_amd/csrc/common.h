@@ -21,6 +21,7 @@ struct pa_prefill_args {
   int64_t seq_len;   // keys in the context (q_start + rows of Q)
   int64_t q_start;   // position of the first query row; 0 for a whole-sequence prefill
   int64_t kv_rows;   // rows per (batch, KV head) slab of K/V: seq_len, or the capacity of a cache
+  int64_t q_rows;    // rows per (batch, query head) slab of Q/O/LSE; 0: seq_len - q_start
   int32_t nb;      // query blocks: ceil((seq_len - q_start) / block)
   int32_t head_dim;
   float scale;     // softmax scale (natural units)

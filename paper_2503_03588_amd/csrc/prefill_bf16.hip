@@ -800,7 +800,7 @@ int pa_launch_prefill_bf16(const pa_prefill_args& a) {
   if (!p.dense && (int64_t)a.max_k * p.subs > TILE_CAP) return POWATTN_UNSUPPORTED;
   if (a.seq_len > 0x7fffffffLL - 1024) return POWATTN_UNSUPPORTED;   // key positions are kept in 32 bits
   p.N = a.seq_len;
-  p.q_start = a.q_start; p.q_rows = a.seq_len - a.q_start; p.kv_rows = a.kv_rows; p.i0 = (int32_t)(a.q_start / a.pat.block);
+  p.q_start = a.q_start; p.q_rows = a.q_rows > 0 ? a.q_rows : a.seq_len - a.q_start; p.kv_rows = a.kv_rows; p.i0 = (int32_t)(a.q_start / a.pat.block);
   p.c2 = a.scale * 1.44269504088896340736f;
   const int64_t tasks = (int64_t)p.G * p.B / QW;
   if (tasks > (1 << 20)) return POWATTN_UNSUPPORTED;

@@ -143,6 +143,25 @@ def test_prefill_chunk_argument_errors(L):
     assert _chunk(L, pat=pa.Pattern(64, 1, 0, flags=pa.DENSE), cnt=None, idx=None, max_k=0, q=None) == pa.INVALID_ARG
 
 
+def test_prefill_varlen_argument_errors(L):
+    cp = pa.Pattern(64, 4, 1).c()
+    lens = (ctypes.c_int64 * 2)(1000, 2048)
+
+    def call(q=FAKE, lens_=lens, npad=2048, hq=4, hkv=2, d=128, dtype=pa.BF16, max_k=13, cnt=FAKE, pat=cp):
+        return L.powattn_prefill_varlen(ctypes.byref(pat), cnt, FAKE, max_k, q, FAKE, FAKE, FAKE, None, 2, hq, hkv,
+                                        lens_, npad, d, dtype, 0.0, None)
+    assert call(q=None) == pa.INVALID_ARG
+    assert call(lens_=None) == pa.INVALID_ARG
+    assert call(cnt=None) == pa.INVALID_ARG
+    assert call(npad=0) == pa.INVALID_ARG
+    assert call(hq=6, hkv=4) == pa.INVALID_ARG
+    assert call(npad=2000) == pa.INVALID_ARG                       # a sequence longer than the padding
+    assert call(lens_=(ctypes.c_int64 * 2)(-1, 5)) == pa.INVALID_ARG
+    assert call(dtype=pa.F32) == pa.UNSUPPORTED
+    assert call(d=96) == pa.UNSUPPORTED
+    assert call(pat=pa.Pattern(48, 4, 1).c()) == pa.UNSUPPORTED
+
+
 def test_decode_argument_errors(L):
     assert _decode(L, q=None) == pa.INVALID_ARG
     assert _decode(L, k=None) == pa.INVALID_ARG
