@@ -3,9 +3,9 @@
 
 One "step" = one pass of the method's path over one batch of synthetic input:
   block-index generation (powattn_mask_build)
-  + sparse prefill at 128K context (BASELINE configuration 3: batch 1, 32 query / 8 KV heads,
+  + sparse prefill at 128K context (configuration 3: batch 1, 32 query / 8 KV heads,
     head_dim 128, seq 131072, block 128, window 4, sink 1, bf16 N(0,1))
-  + one decode step (BASELINE configuration 4: batch 16, 32/8 heads, 65536-token bf16 caches,
+  + one decode step (configuration 4: batch 16, 32/8 heads, 65536-token bf16 caches,
     block 64, window 4, sink 1), rotating over several distinct caches so the reads come from HBM.
 The in-library dense causal kernel (the comparison leg) and the CPU oracle are timed outside
 the timed region.  Prints ONE JSON line.
@@ -237,7 +237,7 @@ def main():
                           "block_pair_ratio": round((nbs * (nbs + 1) / 2) / int(c_s.sum().item()), 2)})
             del qs, ks_, vs_, os_
 
-    # ---------------- layer stack (BASELINE configuration 5): 28 successive sparse-attention layers, 28 query /
+    # ---------------- layer stack (configuration 5): 28 successive sparse-attention layers, 28 query /
     # 4 KV heads, 64K context, block 64, fresh random Q/K/V per layer (no projection weights exist, so the layers
     # are not chained); per-layer kernel time.  Second pass: the hybrid schedule of Section 4.3, in which 2 of
     # every 7 layers keep full attention.  Outside the timed region. ----------------

@@ -94,7 +94,7 @@ def test_custom_block_lists_are_honoured():
 
 
 @pytest.mark.parametrize("cfg", [
-    # name, batch, hq, hkv, n, d, B, W : BASELINE configurations 2, 3 and one layer of 5 at full size
+    # name, batch, hq, hkv, n, d, B, W : the task's configurations 2, 3 and one layer of 5 at full size
     ("prefill_32k", 1, 32, 8, 32768, 128, 64, 4),
     ("long_128k", 1, 32, 8, 131072, 128, 128, 4),
     ("stack_64k", 1, 28, 4, 65536, 128, 64, 4),
