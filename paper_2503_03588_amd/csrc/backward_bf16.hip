@@ -39,6 +39,7 @@ typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8;
 constexpr int KT = 64;            // rows per staged tile
 constexpr int TILE_CAP = 2048;    // tiles per query block in the dq kernel
 constexpr int PART = 16;          // query blocks per part of a sink block's column
+constexpr int PFD = 2;            // matrix instructions per group of LDS fragment reads
 constexpr int NSTG = 2;           // LDS stages of the tile stream: copies run NSTG-1 tiles ahead of the products (3 was
                                   // slower: the extra LDS halves the workgroups per compute unit at block 64)
 constexpr float LOG2E = 1.44269504088896340736f;
@@ -143,6 +144,30 @@ __device__ __forceinline__ void reg_rows(const __bf16* row, bool ok, int lane, b
     f[c] = ok ? *reinterpret_cast<const bf16x8*>(row + 16 * c + 8 * hh) : z;
   }
 }
+// N matrix instructions whose A operands come from LDS, software-pipelined with scheduling barriers (left alone,
+// the compiler reads each fragment right before its use into the same registers, and a wavefront that is alone on
+// its SIMD waits out every LDS latency).
+template <int N, int GRP, class LoadF, class MmaF>
+__device__ __forceinline__ void pipelined_mfma(LoadF load, MmaF mma) {
+  // groups of GRP instructions: the reads of the next group go out together before the current group's matrix
+  // instructions, so that one wait serves a whole group
+  static_assert(N % GRP == 0, "instructions must come in whole groups");
+  bf16x8 fr[N];
+#pragma unroll
+  for (int m = 0; m < GRP; ++m) fr[m] = load(m);
+#pragma unroll
+  for (int g = 0; g < N / GRP; ++g) {
+    if (g + 1 < N / GRP) {
+#pragma unroll
+      for (int j = 0; j < GRP; ++j) fr[(g + 1) * GRP + j] = load((g + 1) * GRP + j);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < GRP; ++j) mma(g * GRP + j, fr[g * GRP + j]);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
 // Element rg (0..15) of a 32x32 accumulator is row 8(rg/4) + 4(lane/32) + rg%4, column lane%32.
 __device__ __forceinline__ int acc_row(int rg, int hh) { return 8 * (rg >> 2) + 4 * hh + (rg & 3); }
 
@@ -260,15 +285,17 @@ __global__ __launch_bounds__(64 * NW) void pa_bwd_dq_kernel(bwd_params p) {
     const uint32_t kt = lds0 + (t % NSTG) * STAGEB, vt = kt + G::TILEB;
     f32x16 S[2], dP[2];
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt) {
+    for (int rt = 0; rt < 2; ++rt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) { S[rt][r] = 0.f; dP[rt][r] = 0.f; }
-#pragma unroll
-      for (int c = 0; c < NC; ++c) {
-        S[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag<D>(kt, c, rt, lane), qf[c], S[rt], 0, 0, 0);
-        dP[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag<D>(vt, c, rt, lane), dof[c], dP[rt], 0, 0, 0);
-      }
-    }
+    // instruction m: d-step c = m/4, key half rt = (m/2)%2, S (K tile) or dP (V tile) = m%2: four independent chains
+    pipelined_mfma<4 * NC, PFD>(
+        [&](int m) { return row_frag<D>((m & 1) ? vt : kt, m >> 2, (m >> 1) & 1, lane); },
+        [&](int m, bf16x8 a) {
+          const int c = m >> 2, rt = (m >> 1) & 1;
+          if (m & 1) dP[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, dof[c], dP[rt], 0, 0, 0);
+          else S[rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[c], S[rt], 0, 0, 0);
+        });
     // dS^T = P^T * (dP^T - Delta), packed to bf16 in the B-operand order of the next product
     u32x4 ds[4];
     // Only tiles that reach the diagonal or the end of the sequence need the mask (wavefront-uniform test); the
@@ -295,11 +322,11 @@ __global__ __launch_bounds__(64 * NW) void pa_bwd_dq_kernel(bwd_params p) {
     };
     if ((int64_t)key0 + KT - 1 > (int64_t)i * p.B + sl * 32 || (int64_t)key0 + KT > p.N) elements(std::true_type{});
     else elements(std::false_type{});
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-      for (int dt = 0; dt < ND; ++dt)
-        acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag<D>(kt, kk, dt, lane), __builtin_bit_cast(bf16x8, ds[kk]), acc[dt], 0, 0, 0);
+    pipelined_mfma<4 * ND, PFD>(
+        [&](int m) { return tr_frag<D>(kt, m / ND, m % ND, lane); },
+        [&](int m, bf16x8 a) {
+          acc[m % ND] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, ds[m / ND]), acc[m % ND], 0, 0, 0);
+        });
   }
   wait_vmcnt<0>();
 
@@ -382,15 +409,22 @@ __global__ __launch_bounds__(64 * NW) void pa_bwd_dkv_kernel(bwd_params p) {
 
   // tile sequence: entry e, query head g of the group, 64-query piece u of the block
   const int n_tiles = n_ent * p.G * p.subs;
-  auto locate = [&](int t, int& i, int& h, int64_t& q0) {
-    const int u = t % p.subs, gg = (t / p.subs) % p.G, e = t / (p.subs * p.G);
-    i = entry(e);
-    h = kvh * p.G + gg;
-    q0 = (int64_t)i * p.B + u * KT;
+  // Two cursors walk it, one for the copies (ahead) and one for the products; they advance digit by digit, so
+  // that the loop has no divisions.
+  struct cursor_t { int u, gg, e; };
+  auto advance = [&](cursor_t& c) {
+    if (++c.u == p.subs) { c.u = 0; if (++c.gg == p.G) { c.gg = 0; ++c.e; } }
   };
+  auto locate = [&](const cursor_t& c, int& i, int& h, int64_t& q0) {
+    i = entry(c.e);
+    h = kvh * p.G + c.gg;
+    q0 = (int64_t)i * p.B + c.u * KT;
+  };
+  cursor_t cf = {0, 0, 0}, cc = {0, 0, 0};
   auto fill = [&](int t) {
     int i, h; int64_t q0;
-    locate(t, i, h, q0);
+    locate(cf, i, h, q0);
+    advance(cf);
     const uint32_t dst = lds0 + (t % NSTG) * STAGEB;
     const int64_t head_rows = ((int64_t)b * p.hq + h) * p.N;
     copy_tile<D, NW>(p.q + head_rows * D, q0, p.N - 1, dst, wave, lane);
@@ -419,7 +453,8 @@ __global__ __launch_bounds__(64 * NW) void pa_bwd_dkv_kernel(bwd_params p) {
     __syncthreads();
     if (t + NSTG - 1 < n_tiles) fill(t + NSTG - 1);
     int i, h; int64_t q0;
-    locate(t, i, h, q0);
+    locate(cc, i, h, q0);
+    advance(cc);
     const uint32_t qt = lds0 + (t % NSTG) * STAGEB, dot = qt + G::TILEB;
     const float* vec = reinterpret_cast<const float*>(smem + (t % NSTG) * STAGEB + 2 * G::TILEB);
 #pragma unroll
@@ -429,11 +464,12 @@ __global__ __launch_bounds__(64 * NW) void pa_bwd_dkv_kernel(bwd_params p) {
       f32x16 S, dP;
 #pragma unroll
       for (int r = 0; r < 16; ++r) { S[r] = 0.f; dP[r] = 0.f; }
-#pragma unroll
-      for (int c = 0; c < NC; ++c) {
-        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag<D>(qt, c, half, lane), kf[c], S, 0, 0, 0);
-        dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(row_frag<D>(dot, c, half, lane), vf[c], dP, 0, 0, 0);
-      }
+      pipelined_mfma<2 * NC, PFD>(
+          [&](int m) { return row_frag<D>((m & 1) ? dot : qt, m >> 1, half, lane); },
+          [&](int m, bf16x8 a) {
+            if (m & 1) dP = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, vf[m >> 1], dP, 0, 0, 0);
+            else S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[m >> 1], S, 0, 0, 0);
+          });
       u32x4 pp[2], dsp[2];
       auto elements = [&](auto masked) {
 #pragma unroll
@@ -465,13 +501,14 @@ __global__ __launch_bounds__(64 * NW) void pa_bwd_dkv_kernel(bwd_params p) {
       // the mask matters on the diagonal block and where queries or keys run past the sequence (uniform test)
       if (i == j || q0 + KT > p.N || ((int64_t)j + 1) * p.B > p.N) elements(std::true_type{});
       else elements(std::false_type{});
-#pragma unroll
-      for (int k2 = 0; k2 < 2; ++k2)
-#pragma unroll
-        for (int dt = 0; dt < ND; ++dt) {
-          dvt[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag<D>(dot, 2 * half + k2, dt, lane), __builtin_bit_cast(bf16x8, pp[k2]), dvt[dt], 0, 0, 0);
-          dkt[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tr_frag<D>(qt, 2 * half + k2, dt, lane), __builtin_bit_cast(bf16x8, dsp[k2]), dkt[dt], 0, 0, 0);
-        }
+      // instruction m: 16-query step k2 = m / (2 ND), d tile dt = (m/2) % ND, dV (dO tile) or dK (Q tile) = m%2
+      pipelined_mfma<4 * ND, PFD>(
+          [&](int m) { return tr_frag<D>((m & 1) ? qt : dot, 2 * half + m / (2 * ND), (m >> 1) % ND, lane); },
+          [&](int m, bf16x8 a) {
+            const int k2 = m / (2 * ND), dt = (m >> 1) % ND;
+            if (m & 1) dkt[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, dsp[k2]), dkt[dt], 0, 0, 0);
+            else dvt[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, pp[k2]), dvt[dt], 0, 0, 0);
+          });
     }
   }
   wait_vmcnt<0>();
