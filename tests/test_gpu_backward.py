@@ -106,3 +106,15 @@ def test_prefill_configuration_size_on_sampled_rows_and_keys():
             err, bar = np.abs(g - ref).max(), TOL_G * max(1.0, np.abs(ref).max())
             print(f"  kv head {kvh} {name}: max abs err {err:.3e} (largest entry {np.abs(ref).max():.3f})", flush=True)
             assert err <= bar, (kvh, name, err, bar)
+
+
+@pytest.mark.parametrize("B,W,S,flags,hq,hkv,n,d", [
+    (64, 4, 1, pa.POWER, 2, 1, 1, 128),           # a single token
+    (64, 4, 1, pa.POWER, 2, 2, 65, 64),           # one token into the second block
+    (64, 2, 8, pa.POWER, 2, 1, 300, 128),         # more sink blocks than blocks: every column is whole
+    (64, 40, 0, pa.POWER, 4, 1, 1100, 128),       # the window covers the whole sequence (full causal attention)
+    (128, 1, 1, 0, 16, 1, 700, 64),               # GQA 16, window of the diagonal block only
+    (256, 2, 1, pa.POWER, 1, 1, 2100, 128),       # one head, block 256, ragged
+])
+def test_degenerate_shapes(B, W, S, flags, hq, hkv, n, d):
+    run_backward(pa.Pattern(B, W, S, flags), 1, hq, hkv, n, d, seed=57)
