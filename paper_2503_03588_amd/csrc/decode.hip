@@ -9,8 +9,9 @@
 // after the loads short.
 //
 //  * A workgroup of 8 wavefronts owns one (sequence, KV head[, split]).  The
-//    attended tokens are cut into 64-token chunks; wavefront w takes chunks
-//    w, w+8, ... and issues all K and V loads of a chunk before touching any.
+//    attended tokens are cut into 64-token chunks, dealt round-robin to the
+//    splits and their wavefronts; a wavefront issues all K and V loads of a
+//    chunk before touching any.
 //  * Everything stays in registers.  K rows are loaded straight into the
 //    A-operand layout of v_mfma_f32_16x16x32_bf16 (S^T = K q^T, the G query
 //    heads of the group are the 16 columns, unused ones zero).  V is loaded
@@ -120,7 +121,9 @@ __global__ __launch_bounds__(64 * NW) void pa_decode_kernel(dec_params p) {
   const __bf16* kslab = p.k + ((int64_t)b * p.hkv + kvh) * p.capacity * D;
   const __bf16* vslab = p.v + ((int64_t)b * p.hkv + kvh) * p.capacity * D;
 
-  for (int slot = split * NW + wave; slot < n_slots; slot += p.splits * NW) {
+  // chunks are dealt round-robin to the splits (slot = wave * splits + split), so that the workgroups of a
+  // (sequence, KV head) stream nearly equal amounts (13 chunks over 2 workgroups: 7 + 6 instead of 8 + 5)
+  for (int slot = wave * p.splits + split; slot < n_slots; slot += p.splits * NW) {
     const int64_t tok0 = block_at(slot / p.subs) * p.B + (int64_t)(slot % p.subs) * CH;
     const int64_t left = t + 1 - tok0;                 // causal: tokens tok0..t are attended
     if (left <= 0) continue;                           // chunk of the diagonal block beyond the query
