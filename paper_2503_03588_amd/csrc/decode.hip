@@ -91,26 +91,24 @@ __global__ __launch_bounds__(64 * NW) void pa_decode_kernel(dec_params p) {
   // Row i in closed form: [0, sink_end) ++ {i - 2^k inside [pow_lo, win_start), k descending} ++ [win_start, i].
   // All of this is uniform over the workgroup, so it runs on the scalar unit of every wavefront.
   const pa_row_shape rs = pa_shape_of_row(p.W, p.S, p.flags, i);
-  int n_pow = 0;
-  int64_t p_top = 1;                       // largest power of two <= i
-  while ((p_top << 1) <= i) p_top <<= 1;
-  if (p.flags & POWATTN_POWER)
-    for (int64_t pw = p_top; pw >= 1; pw >>= 1) {
-      const int64_t jj = i - pw;
-      n_pow += (jj >= rs.pow_lo && jj < rs.win_start) ? 1 : 0;
+  // The isolated blocks i - 2^k lie inside [pow_lo, win_start) exactly for i - win_start < 2^k <= i - pow_lo:
+  // a contiguous range of exponents, found with two leading-zero counts instead of a loop over the powers.
+  int n_pow = 0, k_max = 0;
+  if (p.flags & POWATTN_POWER) {
+    const int64_t below = i - rs.win_start, upto = i - rs.pow_lo;
+    if (upto >= 1) {
+      const int k_min = below > 0 ? 64 - __builtin_clzll((unsigned long long)below) : 0;
+      k_max = 63 - __builtin_clzll((unsigned long long)upto);
+      n_pow = k_max >= k_min ? k_max - k_min + 1 : 0;
     }
+  }
   const int n_blocks = (int)rs.sink_end + n_pow + (int)(i - rs.win_start + 1);
   const int n_slots = n_blocks * p.subs;
-  auto block_at = [&](int lp) -> int64_t {   // lp-th attended block of the row
+  auto block_at = [&](int lp) -> int64_t {   // lp-th attended block of the row, ascending
     if (lp < rs.sink_end) return lp;
     lp -= (int)rs.sink_end;
     if (lp >= n_pow) return rs.win_start + (lp - n_pow);
-    int seen = 0;
-    for (int64_t pw = p_top; pw >= 1; pw >>= 1) {
-      const int64_t jj = i - pw;
-      if (jj >= rs.pow_lo && jj < rs.win_start) { if (seen == lp) return jj; ++seen; }
-    }
-    return i;                                // not reached
+    return i - ((int64_t)1 << (k_max - lp));
   };
 
   float m_run = -INFINITY, l_run = 0.f;
