@@ -48,6 +48,7 @@ struct dec_params {
   int64_t capacity;
   int32_t B, W, S; uint32_t flags;
   int32_t hq, hkv, G, splits, subs;
+  uint32_t subs_magic;  // ceil(2^32 / subs) for subs > 1: slot / subs = umulhi(slot, subs_magic) for every slot of a row
   int32_t fused;        // 1: the last workgroup of a (sequence, KV head) merges the partials itself
   int32_t region;       // which set of arrival counters this call uses
   float c2;
@@ -77,7 +78,11 @@ __global__ __launch_bounds__(64 * NW) void pa_decode_kernel(dec_params p) {
   if (len < 1) len = 1;
   if (len > p.capacity) len = p.capacity;
   const int64_t t = len - 1;
-  const int64_t i = t / p.B;
+  // t / B = (t / 64) / subs, through the same multiply-high as the slots while the quotient is exact
+  static_assert(CH == 64, "the block index is formed from 64-token chunks");
+  const int64_t chunk_of_t = t >> 6;
+  const int64_t i = p.subs == 1 ? chunk_of_t
+                  : chunk_of_t < (1 << 25) ? (int64_t)__umulhi((unsigned)chunk_of_t, p.subs_magic) : chunk_of_t / p.subs;
 
   // q^T fragments: column g, 8 consecutive d per 32-wide step
   bf16x8 qf[NC];
@@ -122,7 +127,11 @@ __global__ __launch_bounds__(64 * NW) void pa_decode_kernel(dec_params p) {
   // chunks are dealt round-robin to the splits (slot = wave * splits + split), so that the workgroups of a
   // (sequence, KV head) stream nearly equal amounts (13 chunks over 2 workgroups: 7 + 6 instead of 8 + 5)
   for (int slot = wave * p.splits + split; slot < n_slots; slot += p.splits * NW) {
-    const int64_t tok0 = block_at(slot / p.subs) * p.B + (int64_t)(slot % p.subs) * CH;
+    // (no division in the kernel: a 64-bit one costs more than the rest of the address arithmetic)
+    const int lp = p.subs == 1 ? slot : (int)__umulhi((unsigned)slot, p.subs_magic);
+    const int sub = slot - lp * p.subs;
+    const int64_t blk = block_at(lp);
+    const int64_t tok0 = blk * p.B + (int64_t)sub * CH;
     const int64_t left = t + 1 - tok0;                 // causal: tokens tok0..t are attended
     if (left <= 0) continue;                           // chunk of the diagonal block beyond the query
     const int n_tok = left >= CH ? CH : (int)left;
@@ -132,10 +141,10 @@ __global__ __launch_bounds__(64 * NW) void pa_decode_kernel(dec_params p) {
       // Paged cache: the block's page comes from the table (one more dependent look-up); a page holds the
       // block's tokens of every KV head.  A page number outside the pool is clamped into it: a bad table gives
       // wrong numbers, never an access outside the pool.
-      const int64_t blk = tok0 / p.B;                  // < table_stride, because len <= table_stride * B
+      // blk < table_stride, because len <= table_stride * B
       int64_t page = p.block_table[(int64_t)b * p.table_stride + blk];
       page = page < 0 ? 0 : (page >= p.n_pages ? p.n_pages - 1 : page);
-      const int64_t off = ((page * p.hkv + kvh) * p.B + (tok0 - blk * p.B)) * D;
+      const int64_t off = ((page * p.hkv + kvh) * p.B + (int64_t)sub * CH) * D;
       kb = p.k + off;
       vb = p.v + off;
     }
@@ -381,6 +390,7 @@ int pa_launch_decode_bf16(const pa_decode_args& a) {
   p.capacity = a.capacity;
   p.B = a.pat.block; p.W = a.pat.window; p.S = a.pat.sink; p.flags = a.pat.flags;
   p.hq = a.hq; p.hkv = a.hkv; p.G = a.hq / a.hkv; p.splits = a.n_split; p.subs = a.pat.block / CH;
+  p.subs_magic = p.subs > 1 ? (uint32_t)(((1ull << 32) + p.subs - 1) / p.subs) : 0u;
   p.c2 = a.scale * 1.44269504088896340736f;
   p.block_table = a.block_table; p.table_stride = a.table_stride; p.n_pages = a.n_pages;
   static std::atomic<unsigned> next_region{0};
