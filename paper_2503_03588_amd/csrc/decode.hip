@@ -63,10 +63,170 @@ struct dec_params {
 constexpr int CTR_SETS = 64, CTR_PER_SET = 4096;
 __device__ unsigned int g_arrivals[CTR_SETS][CTR_PER_SET];
 
+// The query's row of the pattern in closed form: [0, sink_end) ++ {i - 2^k inside [pow_lo, win_start), k
+// descending} ++ [win_start, i].  Uniform over a workgroup, so all of it runs on the scalar unit.
+struct dec_row {
+  pa_row_shape rs;
+  int64_t t, i;          // position of the query, its block
+  int n_pow, k_max;      // isolated blocks i - 2^k for k = k_max, k_max-1, ...: n_pow of them
+  int n_slots;           // 64-token chunks of the attended blocks
+};
+__device__ __forceinline__ dec_row dec_row_of(const dec_params& p, int64_t len) {
+  dec_row r;
+  if (len < 1) len = 1;
+  if (len > p.capacity) len = p.capacity;
+  r.t = len - 1;
+  // t / B = (t / 64) / subs, through the same multiply-high as the slots while the quotient is exact
+  static_assert(CH == 64, "the block index is formed from 64-token chunks");
+  const int64_t chunk_of_t = r.t >> 6;
+  r.i = p.subs == 1 ? chunk_of_t
+      : chunk_of_t < (1 << 25) ? (int64_t)__umulhi((unsigned)chunk_of_t, p.subs_magic) : chunk_of_t / p.subs;
+  r.rs = pa_shape_of_row(p.W, p.S, p.flags, r.i);
+  // The isolated blocks i - 2^k lie inside [pow_lo, win_start) exactly for i - win_start < 2^k <= i - pow_lo:
+  // a contiguous range of exponents, found with two leading-zero counts instead of a loop over the powers.
+  r.n_pow = 0; r.k_max = 0;
+  if (p.flags & POWATTN_POWER) {
+    const int64_t below = r.i - r.rs.win_start, upto = r.i - r.rs.pow_lo;
+    if (upto >= 1) {
+      const int k_min = below > 0 ? 64 - __builtin_clzll((unsigned long long)below) : 0;
+      r.k_max = 63 - __builtin_clzll((unsigned long long)upto);
+      r.n_pow = r.k_max >= k_min ? r.k_max - k_min + 1 : 0;
+    }
+  }
+  const int n_blocks = (int)r.rs.sink_end + r.n_pow + (int)(r.i - r.rs.win_start + 1);
+  r.n_slots = n_blocks * p.subs;
+  return r;
+}
+__device__ __forceinline__ int64_t dec_block_at(const dec_row& r, int lp) {   // lp-th attended block, ascending
+  if (lp < r.rs.sink_end) return lp;
+  lp -= (int)r.rs.sink_end;
+  if (lp >= r.n_pow) return r.rs.win_start + (lp - r.n_pow);
+  return r.i - ((int64_t)1 << (r.k_max - lp));
+}
+// Chunk `slot` of the row: its block, the chunk inside the block, the tokens of it the query attends (<= 0: none)
+struct dec_place { int64_t blk; int sub; int n_tok; };
+__device__ __forceinline__ dec_place dec_place_of(const dec_params& p, const dec_row& r, int slot) {
+  // (no division in the kernel: a 64-bit one costs more than the rest of the address arithmetic)
+  dec_place c;
+  const int lp = p.subs == 1 ? slot : (int)__umulhi((unsigned)slot, p.subs_magic);
+  c.sub = slot - lp * p.subs;
+  c.blk = dec_block_at(r, lp);
+  const int64_t left = r.t + 1 - (c.blk * p.B + (int64_t)c.sub * CH);      // causal: tokens tok0..t are attended
+  c.n_tok = left >= CH ? CH : (int)left;
+  return c;
+}
+// First K and V row of a chunk: in the contiguous cache, or in its page (page numbers outside the pool are clamped
+// into it: a bad table gives wrong numbers, never an access outside the pool)
+__device__ __forceinline__ int64_t dec_chunk_offset(const dec_params& p, int b, int kvh, const dec_place& c, int64_t page, int D) {
+  if (!p.block_table) return (((int64_t)b * p.hkv + kvh) * p.capacity + c.blk * p.B + (int64_t)c.sub * CH) * D;
+  page = page < 0 ? 0 : (page >= p.n_pages ? p.n_pages - 1 : page);
+  return ((page * p.hkv + kvh) * p.B + (int64_t)c.sub * CH) * D;
+}
+
+// The registers of one 64-token chunk: every load of it is issued before any is used.
+template <int D>
+struct dec_chunk {
+  u32x4 kraw[4][D / 32];
+  u32x4 vraw[2][8];
+};
+// K tile 2x+y, row rho = lane%16 holds token 32x + 8(rho/4) + 4y + rho%4: with this order the S^T
+// accumulator of lane (g, q4) holds tokens 32x + 8*q4 + (0..7), which is what P^T must supply below.
+// V: lane (dg = lane%16, tg = lane/16) takes tokens 32x + 8tg + (0..7), d = 8dg .. 8dg+7.
+template <int D>
+__device__ __forceinline__ void dec_issue(dec_chunk<D>& c, const __bf16* kb, const __bf16* vb, int n_tok, int g, int q4) {
+  constexpr int NC = D / 32, CPR = D / 8;
+#pragma unroll
+  for (int tau = 0; tau < 4; ++tau) {
+    const int tk = 32 * (tau >> 1) + 8 * (g >> 2) + 4 * (tau & 1) + (g & 3);
+#pragma unroll
+    for (int cc = 0; cc < NC; ++cc)
+      c.kraw[tau][cc] = tk < n_tok ? *reinterpret_cast<const u32x4*>(kb + tk * D + 32 * cc + 8 * q4) : u32x4{0, 0, 0, 0};
+  }
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+      const int tk = 32 * x + 8 * q4 + r;
+      c.vraw[x][r] = (g < CPR && tk < n_tok) ? *reinterpret_cast<const u32x4*>(vb + tk * D + 8 * g) : u32x4{0, 0, 0, 0};
+    }
+}
+// One online-softmax update with the chunk: S^T = K q^T, then O^T += V^T P^T.
+template <int D>
+__device__ __forceinline__ void dec_consume(const dec_chunk<D>& c, const bf16x8 (&qf)[D / 32], int n_tok, float c2, int q4,
+                                            float& m_run, float& l_run, f32x4 (&O)[8]) {
+  constexpr int NC = D / 32;
+  f32x4 S[4];
+#pragma unroll
+  for (int tau = 0; tau < 4; ++tau) {
+    S[tau] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int cc = 0; cc < NC; ++cc)
+      S[tau] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, c.kraw[tau][cc]), qf[cc], S[tau], 0, 0, 0);
+  }
+  // ---- online softmax; S[2x+y][r] is token 32x + 8*q4 + 4y + r of head g ----
+  float mx = -INFINITY;
+#pragma unroll
+  for (int tau = 0; tau < 4; ++tau)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int tk = 32 * (tau >> 1) + 8 * q4 + 4 * (tau & 1) + r;
+      S[tau][r] = tk < n_tok ? S[tau][r] * c2 : -INFINITY;
+      mx = fmaxf(mx, S[tau][r]);
+    }
+  mx = fmaxf(mx, __shfl_xor(mx, 16));
+  mx = fmaxf(mx, __shfl_xor(mx, 32));                // finite: token 0 of the chunk is attended
+  const float m_new = fmaxf(m_run, mx);
+  const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+  m_run = m_new;
+  float rowsum = 0.f;
+#pragma unroll
+  for (int tau = 0; tau < 4; ++tau)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      S[tau][r] = __builtin_amdgcn_exp2f(S[tau][r] - m_new);
+      rowsum += S[tau][r];
+    }
+  l_run = l_run * alpha + rowsum;
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) O[j][r] *= alpha;
+
+  // ---- O^T += V^T P^T: 32 tokens per step; MFMA j covers d = 8*row + j ----
+#pragma unroll
+  for (int x = 0; x < 2; ++x) {
+    bf16x8 pf;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) pf[e] = (__bf16)S[2 * x + (e >> 2)][e & 3];
+    // transpose the lane's 8 tokens x 8 d block: pairs of tokens share a dword
+    uint32_t tr[4][8];                                // tr[a][d]: tokens 2a, 2a+1 at d
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+      for (int kd = 0; kd < 4; ++kd) {
+        const uint32_t r0 = c.vraw[x][2 * a][kd], r1 = c.vraw[x][2 * a + 1][kd];
+        tr[a][2 * kd] = __builtin_amdgcn_perm(r1, r0, 0x05040100u);       // low halves: d = 2kd
+        tr[a][2 * kd + 1] = __builtin_amdgcn_perm(r1, r0, 0x07060302u);   // high halves: d = 2kd+1
+      }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const u32x4 vf = {tr[0][j], tr[1][j], tr[2][j], tr[3][j]};
+      O[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf), pf, O[j], 0, 0, 0);
+    }
+  }
+}
+// q^T fragments: column g, 8 consecutive d per 32-wide step
+template <int D>
+__device__ __forceinline__ void dec_load_q(bf16x8 (&qf)[D / 32], const dec_params& p, int b, int kvh, int g, int q4) {
+  const bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+  const __bf16* qp = p.q + ((int64_t)b * p.hq + (int64_t)kvh * p.G + (g < p.G ? g : 0)) * D;
+#pragma unroll
+  for (int c = 0; c < D / 32; ++c)
+    qf[c] = g < p.G ? *reinterpret_cast<const bf16x8*>(qp + 32 * c + 8 * q4) : z;
+}
+
 template <int D>
 __global__ __launch_bounds__(64 * NW) void pa_decode_kernel(dec_params p) {
-  constexpr int NC = D / 32;     // 32-wide steps of the head dimension in S^T = K q^T
-  constexpr int CPR = D / 8;     // 16-byte pieces per row; lane%16 >= CPR idles in the V path (D = 64)
   __shared__ float s_m[NW][MAXG], s_l[NW][MAXG];
   extern __shared__ float s_o_dyn[];            // [NW][G][D] partial outputs of the wavefronts
 
@@ -74,163 +234,27 @@ __global__ __launch_bounds__(64 * NW) void pa_decode_kernel(dec_params p) {
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int g = lane & 15, q4 = lane >> 4;    // column (query head) and k-group of this lane
 
-  int64_t len = p.kv_len[b];
-  if (len < 1) len = 1;
-  if (len > p.capacity) len = p.capacity;
-  const int64_t t = len - 1;
-  // t / B = (t / 64) / subs, through the same multiply-high as the slots while the quotient is exact
-  static_assert(CH == 64, "the block index is formed from 64-token chunks");
-  const int64_t chunk_of_t = t >> 6;
-  const int64_t i = p.subs == 1 ? chunk_of_t
-                  : chunk_of_t < (1 << 25) ? (int64_t)__umulhi((unsigned)chunk_of_t, p.subs_magic) : chunk_of_t / p.subs;
-
-  // q^T fragments: column g, 8 consecutive d per 32-wide step
-  bf16x8 qf[NC];
-  {
-    const bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-    const __bf16* qp = p.q + ((int64_t)b * p.hq + (int64_t)kvh * p.G + (g < p.G ? g : 0)) * D;
-#pragma unroll
-    for (int c = 0; c < NC; ++c)
-      qf[c] = g < p.G ? *reinterpret_cast<const bf16x8*>(qp + 32 * c + 8 * q4) : z;
-  }
-  // Row i in closed form: [0, sink_end) ++ {i - 2^k inside [pow_lo, win_start), k descending} ++ [win_start, i].
-  // All of this is uniform over the workgroup, so it runs on the scalar unit of every wavefront.
-  const pa_row_shape rs = pa_shape_of_row(p.W, p.S, p.flags, i);
-  // The isolated blocks i - 2^k lie inside [pow_lo, win_start) exactly for i - win_start < 2^k <= i - pow_lo:
-  // a contiguous range of exponents, found with two leading-zero counts instead of a loop over the powers.
-  int n_pow = 0, k_max = 0;
-  if (p.flags & POWATTN_POWER) {
-    const int64_t below = i - rs.win_start, upto = i - rs.pow_lo;
-    if (upto >= 1) {
-      const int k_min = below > 0 ? 64 - __builtin_clzll((unsigned long long)below) : 0;
-      k_max = 63 - __builtin_clzll((unsigned long long)upto);
-      n_pow = k_max >= k_min ? k_max - k_min + 1 : 0;
-    }
-  }
-  const int n_blocks = (int)rs.sink_end + n_pow + (int)(i - rs.win_start + 1);
-  const int n_slots = n_blocks * p.subs;
-  auto block_at = [&](int lp) -> int64_t {   // lp-th attended block of the row, ascending
-    if (lp < rs.sink_end) return lp;
-    lp -= (int)rs.sink_end;
-    if (lp >= n_pow) return rs.win_start + (lp - n_pow);
-    return i - ((int64_t)1 << (k_max - lp));
-  };
+  const dec_row row = dec_row_of(p, p.kv_len[b]);
+  bf16x8 qf[D / 32];
+  dec_load_q<D>(qf, p, b, kvh, g, q4);
 
   float m_run = -INFINITY, l_run = 0.f;
   f32x4 O[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) O[j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  const __bf16* kslab = p.k + ((int64_t)b * p.hkv + kvh) * p.capacity * D;
-  const __bf16* vslab = p.v + ((int64_t)b * p.hkv + kvh) * p.capacity * D;
-
   // chunks are dealt round-robin to the splits (slot = wave * splits + split), so that the workgroups of a
   // (sequence, KV head) stream nearly equal amounts (13 chunks over 2 workgroups: 7 + 6 instead of 8 + 5)
-  for (int slot = wave * p.splits + split; slot < n_slots; slot += p.splits * NW) {
-    // (no division in the kernel: a 64-bit one costs more than the rest of the address arithmetic)
-    const int lp = p.subs == 1 ? slot : (int)__umulhi((unsigned)slot, p.subs_magic);
-    const int sub = slot - lp * p.subs;
-    const int64_t blk = block_at(lp);
-    const int64_t tok0 = blk * p.B + (int64_t)sub * CH;
-    const int64_t left = t + 1 - tok0;                 // causal: tokens tok0..t are attended
-    if (left <= 0) continue;                           // chunk of the diagonal block beyond the query
-    const int n_tok = left >= CH ? CH : (int)left;
-    const __bf16* kb = kslab + tok0 * D;
-    const __bf16* vb = vslab + tok0 * D;
-    if (p.block_table) {
-      // Paged cache: the block's page comes from the table (one more dependent look-up); a page holds the
-      // block's tokens of every KV head.  A page number outside the pool is clamped into it: a bad table gives
-      // wrong numbers, never an access outside the pool.
-      // blk < table_stride, because len <= table_stride * B
-      int64_t page = p.block_table[(int64_t)b * p.table_stride + blk];
-      page = page < 0 ? 0 : (page >= p.n_pages ? p.n_pages - 1 : page);
-      const int64_t off = ((page * p.hkv + kvh) * p.B + (int64_t)sub * CH) * D;
-      kb = p.k + off;
-      vb = p.v + off;
-    }
-
-    // ---- issue every load of the chunk ----
-    // K tile 2x+y, row rho = lane%16 holds token 32x + 8(rho/4) + 4y + rho%4: with this order the S^T
-    // accumulator of lane (g, q4) holds tokens 32x + 8*q4 + (0..7), which is what P^T must supply below.
-    u32x4 kraw[4][NC];
-#pragma unroll
-    for (int tau = 0; tau < 4; ++tau) {
-      const int tk = 32 * (tau >> 1) + 8 * (g >> 2) + 4 * (tau & 1) + (g & 3);
-#pragma unroll
-      for (int c = 0; c < NC; ++c)
-        kraw[tau][c] = tk < n_tok ? *reinterpret_cast<const u32x4*>(kb + tk * D + 32 * c + 8 * q4) : u32x4{0, 0, 0, 0};
-    }
-    // V: lane (dg = lane%16, tg = lane/16) takes tokens 32x + 8tg + (0..7), d = 8dg .. 8dg+7
-    u32x4 vraw[2][8];
-#pragma unroll
-    for (int x = 0; x < 2; ++x)
-#pragma unroll
-      for (int r = 0; r < 8; ++r) {
-        const int tk = 32 * x + 8 * q4 + r;
-        vraw[x][r] = (g < CPR && tk < n_tok) ? *reinterpret_cast<const u32x4*>(vb + tk * D + 8 * g) : u32x4{0, 0, 0, 0};
-      }
-
-    // ---- S^T = K q^T ----
-    f32x4 S[4];
-#pragma unroll
-    for (int tau = 0; tau < 4; ++tau) {
-      S[tau] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int c = 0; c < NC; ++c)
-        S[tau] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kraw[tau][c]), qf[c], S[tau], 0, 0, 0);
-    }
-
-    // ---- online softmax; S[2x+y][r] is token 32x + 8*q4 + 4y + r of head g ----
-    float mx = -INFINITY;
-#pragma unroll
-    for (int tau = 0; tau < 4; ++tau)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int tk = 32 * (tau >> 1) + 8 * q4 + 4 * (tau & 1) + r;
-        S[tau][r] = tk < n_tok ? S[tau][r] * p.c2 : -INFINITY;
-        mx = fmaxf(mx, S[tau][r]);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));                // finite: token 0 of the chunk is attended
-    const float m_new = fmaxf(m_run, mx);
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-    m_run = m_new;
-    float rowsum = 0.f;
-#pragma unroll
-    for (int tau = 0; tau < 4; ++tau)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        S[tau][r] = __builtin_amdgcn_exp2f(S[tau][r] - m_new);
-        rowsum += S[tau][r];
-      }
-    l_run = l_run * alpha + rowsum;
-#pragma unroll
-    for (int j = 0; j < 8; ++j)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) O[j][r] *= alpha;
-
-    // ---- O^T += V^T P^T: 32 tokens per step; MFMA j covers d = 8*row + j ----
-#pragma unroll
-    for (int x = 0; x < 2; ++x) {
-      bf16x8 pf;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) pf[e] = (__bf16)S[2 * x + (e >> 2)][e & 3];
-      // transpose the lane's 8 tokens x 8 d block: pairs of tokens share a dword
-      uint32_t tr[4][8];                                // tr[a][d]: tokens 2a, 2a+1 at d
-#pragma unroll
-      for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int kd = 0; kd < 4; ++kd) {
-          const uint32_t r0 = vraw[x][2 * a][kd], r1 = vraw[x][2 * a + 1][kd];
-          tr[a][2 * kd] = __builtin_amdgcn_perm(r1, r0, 0x05040100u);       // low halves: d = 2kd
-          tr[a][2 * kd + 1] = __builtin_amdgcn_perm(r1, r0, 0x07060302u);   // high halves: d = 2kd+1
-        }
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const u32x4 vf = {tr[0][j], tr[1][j], tr[2][j], tr[3][j]};
-        O[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf), pf, O[j], 0, 0, 0);
-      }
-    }
+  for (int slot = wave * p.splits + split; slot < row.n_slots; slot += p.splits * NW) {
+    const dec_place pl = dec_place_of(p, row, slot);
+    if (pl.n_tok <= 0) continue;                         // chunk of the diagonal block beyond the query
+    // paged cache: the block's page comes from the table (one more dependent look-up; blk < table_stride,
+    // because len <= table_stride * B); a page holds the block's tokens of every KV head
+    const int64_t page = p.block_table ? p.block_table[(int64_t)b * p.table_stride + pl.blk] : 0;
+    const int64_t off = dec_chunk_offset(p, b, kvh, pl, page, D);
+    dec_chunk<D> c;
+    dec_issue<D>(c, p.k + off, p.v + off, pl.n_tok, g, q4);
+    dec_consume<D>(c, qf, pl.n_tok, p.c2, q4, m_run, l_run, O);
   }
 
   // ---- merge the wavefronts: lane (g, q4) holds O[j][r] = o[g][d = 8(4*q4 + r) + j] ----
