@@ -336,6 +336,121 @@ __global__ __launch_bounds__(64 * NW) void pa_decode_kernel(dec_params p) {
   }
 }
 
+// Large batches: persistent workgroups.  With many more (sequence, KV head, split) items than compute units the
+// kernel above leaves every compute unit without a byte in flight while a workgroup looks its sequence length up and
+// while it merges (one workgroup fits at a time: its wavefronts hold a whole chunk in registers).  Here a workgroup
+// walks through items; a wavefront requests the chunk of the next item as soon as the registers of the current one
+// are free, before the workgroup merges the current item through LDS, and the sequence length and the page of an
+// item are read two and one items ahead.  Partials go to the workspace with plain stores and the merge kernel
+// below combines them after this kernel: no counters, no waits on stores.  Every item is a single pass (the host
+// checks that a row has at most splits * NW chunks).
+template <int D>
+__global__ __launch_bounds__(64 * NW) void pa_decode_stream_kernel(dec_params p, int n_items) {
+  __shared__ float s_m[2][NW][MAXG], s_l[2][NW][MAXG];
+  extern __shared__ float s_o_dyn[];            // [2][NW][G][D] partial outputs of the wavefronts, two items
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane & 15, q4 = lane >> 4;
+  const int stride = (int)gridDim.x;
+  const int per_b = p.hkv * p.splits;
+
+  struct item_t { int b, kvh, split; };
+  auto item_of = [&](int w) -> item_t {
+    item_t it;
+    const int w2 = w < n_items ? w : n_items - 1;          // beyond the end: any valid item (its loads are not issued)
+    it.b = w2 / per_b;
+    const int r = w2 - it.b * per_b;
+    it.kvh = r / p.splits;
+    it.split = r - it.kvh * p.splits;
+    return it;
+  };
+  // where this wavefront's chunk of item w lies, given the sequence length
+  struct plan_t { item_t it; dec_place pl; bool has; };
+  auto plan_of = [&](int w, int len) -> plan_t {
+    plan_t pn;
+    pn.it = item_of(w);
+    const dec_row row = dec_row_of(p, len);
+    const int slot = wave * p.splits + pn.it.split;
+    pn.pl = dec_place_of(p, row, slot < row.n_slots ? slot : 0);
+    pn.has = w < n_items && slot < row.n_slots && pn.pl.n_tok > 0;
+    return pn;
+  };
+  auto page_ptr = [&](const plan_t& pn) -> const int32_t* {
+    return p.block_table ? p.block_table + (int64_t)pn.it.b * p.table_stride + pn.pl.blk : p.kv_len;
+  };
+
+  int w = (int)blockIdx.x;
+  // the scalar pipeline: plan and page of the item after this one, length of the one after that
+  plan_t cur = plan_of(w, p.kv_len[item_of(w).b]);
+  int cur_page = *page_ptr(cur);
+  plan_t nxt = plan_of(w + stride, p.kv_len[item_of(w + stride).b]);
+  int nxt_page = *page_ptr(nxt);
+  int len2 = p.kv_len[item_of(w + 2 * stride).b];
+
+  dec_chunk<D> c;
+  bf16x8 qf[D / 32];
+  auto request = [&](const plan_t& pn, int page) {
+    dec_load_q<D>(qf, p, pn.it.b, pn.it.kvh, g, q4);
+    const int64_t off = dec_chunk_offset(p, pn.it.b, pn.it.kvh, pn.pl, page, D);
+    dec_issue<D>(c, p.k + off, p.v + off, pn.has ? pn.pl.n_tok : 0, g, q4);   // no tokens: no loads
+  };
+  request(cur, cur_page);
+
+  for (int n = 0; w < n_items; w += stride, ++n) {
+    const int buf = n & 1;
+    float* s_o = s_o_dyn + (size_t)buf * NW * p.G * D;
+    // ---- this wavefront's chunk of the current item ----
+    float m_run = -INFINITY, l_run = 0.f;
+    f32x4 O[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) O[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (cur.has) dec_consume<D>(c, qf, cur.pl.n_tok, p.c2, q4, m_run, l_run, O);
+    l_run += __shfl_xor(l_run, 16);
+    l_run += __shfl_xor(l_run, 32);
+    if (g < p.G) {
+      if (q4 == 0) { s_m[buf][wave][g] = m_run; s_l[buf][wave][g] = l_run; }
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int d = 8 * (4 * q4 + r) + j;
+          if (d < D) s_o[((wave * p.G) + g) * D + d] = O[j][r];
+        }
+    }
+    // ---- the next item's bytes are requested before this one is merged ----
+    const item_t done = cur.it;
+    cur = nxt; cur_page = nxt_page;
+    request(cur, cur_page);
+    nxt = plan_of(w + 2 * stride, len2);
+    nxt_page = *page_ptr(nxt);
+    len2 = p.kv_len[item_of(w + 3 * stride).b];
+    __syncthreads();     // the item's partials are in LDS; the other buffer is free again (its readers passed here)
+
+    for (int e = tid; e < p.G * D; e += 64 * NW) {
+      const int gg = e / D, d = e % D;
+      float M = -INFINITY;
+#pragma unroll
+      for (int wv = 0; wv < NW; ++wv) M = fmaxf(M, s_m[buf][wv][gg]);
+      float L = 0.f, acc = 0.f;
+#pragma unroll
+      for (int wv = 0; wv < NW; ++wv) {
+        const float wt = s_l[buf][wv][gg] > 0.f ? __builtin_amdgcn_exp2f(s_m[buf][wv][gg] - M) : 0.f;
+        L = fmaf(wt, s_l[buf][wv][gg], L);
+        acc = fmaf(wt, s_o[((wv * p.G) + gg) * D + d], acc);
+      }
+      const int h = done.kvh * p.G + gg;
+      if (p.splits == 1) {
+        p.o[((int64_t)done.b * p.hq + h) * D + d] = (__bf16)(acc / L);      // L > 0: chunk 0 of the row is never empty
+        if (p.lse && d == 0) p.lse[(int64_t)done.b * p.hq + h] = (M + log2f(L)) * 0.69314718055994530942f;
+      } else {
+        float* part = p.partials + (((int64_t)done.b * p.hq + h) * p.splits + done.split) * (D + 2);
+        part[d] = acc;
+        if (d == 0) { part[D] = M; part[D + 1] = L; }                        // an idle split leaves M = -inf, L = 0
+      }
+    }
+  }
+}
+
 // Merges the partials of the splits: one wavefront per (sequence, query head).  The loads of
 // eight splits are issued together so that their latencies overlap.
 template <int D>
@@ -420,6 +535,46 @@ int pa_launch_decode_bf16(const pa_decode_args& a) {
   static std::atomic<unsigned> next_region{0};
   p.fused = (a.n_split > 1 && a.n_split <= 64 && (int64_t)a.batch * a.hkv <= CTR_PER_SET) ? 1 : 0;
   p.region = p.fused ? (int32_t)(next_region.fetch_add(1) % CTR_SETS) : 0;
+  // Many more items than compute units, every row a single pass: persistent workgroups that keep bytes in flight
+  // across items, then the merge kernel.
+  {
+    static int n_cu[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+    if (n_cu[dev] == 0) {
+      int v = 0;
+      if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1) v = 1;
+      n_cu[dev] = v;
+    }
+    const int64_t items = (int64_t)a.batch * a.hkv * a.n_split;
+    const int64_t max_slots = (int64_t)powattn_max_k(&a.pat, a.capacity) * p.subs;
+    if (items >= 4 * (int64_t)n_cu[dev] && items <= 0x7fffffff / 4 && max_slots <= (int64_t)a.n_split * NW) {
+      p.fused = 0;
+      const size_t lds2 = 2 * (size_t)NW * p.G * a.head_dim * sizeof(float);   // at most 128 KB
+      static bool attr_done[2] = {false, false};
+      const int which = a.head_dim == 128 ? 0 : 1;
+      const void* fn = which == 0 ? reinterpret_cast<const void*>(&pa_decode_stream_kernel<128>)
+                                  : reinterpret_cast<const void*>(&pa_decode_stream_kernel<64>);
+      if (!attr_done[which]) {
+        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(2 * (size_t)NW * MAXG * 128 * sizeof(float)));
+        if (e != hipSuccess) return pa_note_hip(e);
+        attr_done[which] = true;
+      }
+      const dim3 pgrid((uint32_t)n_cu[dev]);
+      if (a.head_dim == 128)
+        hipLaunchKernelGGL((pa_decode_stream_kernel<128>), pgrid, dim3(64 * NW), lds2, a.stream, p, (int)items);
+      else
+        hipLaunchKernelGGL((pa_decode_stream_kernel<64>), pgrid, dim3(64 * NW), lds2, a.stream, p, (int)items);
+      int st = pa_note_hip(hipGetLastError());
+      if (st != POWATTN_OK || a.n_split == 1) return st;
+      dim3 mgrid((uint32_t)a.hq, (uint32_t)a.batch);
+      if (a.head_dim == 128)
+        hipLaunchKernelGGL((pa_decode_merge_kernel<128>), mgrid, dim3(64), 0, a.stream, p);
+      else
+        hipLaunchKernelGGL((pa_decode_merge_kernel<64>), mgrid, dim3(64), 0, a.stream, p);
+      return pa_note_hip(hipGetLastError());
+    }
+  }
   dim3 grid((uint32_t)a.n_split, (uint32_t)a.hkv, (uint32_t)a.batch);
   const size_t lds = (size_t)NW * p.G * a.head_dim * sizeof(float);   // at most 64 KB (G <= 16, D <= 128)
   if (a.head_dim == 128)

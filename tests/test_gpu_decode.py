@@ -136,3 +136,42 @@ def test_back_to_back_calls_on_one_workspace():
     for i in range(40):
         o, _ = pa.decode(pat, *(A if i % 2 == 0 else Bt), lens, workspace=ws)
         assert torch.equal(o, ref_a if i % 2 == 0 else ref_b), i
+
+
+@pytest.mark.parametrize("B,W,S,hq,hkv,d,cap,batch", [
+    (64, 4, 1, 8, 4, 128, 2048, 288),      # 288 x 4 x 2 splits = 2304 work items on 256 compute units
+    (128, 4, 1, 8, 2, 64, 4096, 200),      # two chunks per block, head_dim 64, three splits
+    (64, 3, 2, 4, 4, 128, 1024, 300),      # one query head per KV head
+])
+def test_large_batches_on_persistent_workgroups(B, W, S, hq, hkv, d, cap, batch):
+    # With at least four work items (sequence, KV head, split) per compute unit and every row a single pass, the
+    # library streams the items through persistent workgroups (the next item's loads are issued before the
+    # current one is merged, lengths and pages are read ahead) and merges the splits in a second kernel.  Every
+    # sequence is checked, with lengths at both ends, around block boundaries and at random.
+    pat = pa.Pattern(B, W, S)
+    rng = np.random.default_rng(61)
+    kv_len = rng.integers(1, cap + 1, size=batch)
+    kv_len[:8] = [1, 2, B - 1, B, B + 1, cap, cap - 1, 2 * B]
+    kv_len = [int(x) for x in kv_len]
+    q, k, v = synth.decode_inputs(batch, hq, hkv, cap, d, "bf16", seed=62)
+    lens = torch.tensor(kv_len, dtype=torch.int32).cuda()
+    ws = pa.decode_workspace(pat, batch, hq, hkv, d, cap)
+    ws.fill_(0xFF)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    o, lse = pa.decode(pat, qd, kd, vd, lens, workspace=ws)
+    o2, lse2 = pa.decode(pat, qd, kd, vd, lens, workspace=ws)          # same workspace again: same result
+    torch.cuda.synchronize()
+    assert torch.equal(o, o2) and torch.equal(lse, lse2)
+    go, glse = o.double().cpu().numpy(), lse.double().cpu().numpy()
+    assert np.isfinite(go).all() and np.isfinite(glse).all()
+    oo, olse = orc.decode(synth.to_numpy_storage(q), synth.to_numpy_storage(k), synth.to_numpy_storage(v),
+                          np.asarray(kv_len), oracle_pattern(pat), None)
+    assert np.abs(go - oo).max() <= TOL_O["bf16"]
+    assert np.abs(glse - olse).max() <= TOL_LSE
+    # the same sequences eight at a time take the one-workgroup-per-item kernel: same numbers up to the order
+    # in which the splits are merged
+    for b0 in (0, 8, batch - 8):
+        ob, lb = pa.decode(pat, qd[b0:b0 + 8].contiguous(), kd[b0:b0 + 8].contiguous(), vd[b0:b0 + 8].contiguous(),
+                           lens[b0:b0 + 8].contiguous())
+        assert (ob.float() - o[b0:b0 + 8].float()).abs().max().item() <= 1e-2
+        assert (lb - lse[b0:b0 + 8]).abs().max().item() <= 1e-5

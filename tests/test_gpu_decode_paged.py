@@ -100,3 +100,28 @@ def test_bad_page_numbers_stay_inside_the_pool():
     o, lse = pa.decode_paged(pat, q.cuda(), kp.cuda(), vp.cuda(), table.cuda(), lens)
     torch.cuda.synchronize()
     assert torch.isfinite(o.float()).all() and torch.isfinite(lse).all()
+
+
+def test_paged_large_batch_on_persistent_workgroups():
+    # enough work items for the persistent workgroups; pages are looked up one item ahead there
+    B, W, S, hq, hkv, d, cap, batch = 64, 4, 1, 8, 4, 128, 2048, 272
+    pat = pa.Pattern(B, W, S)
+    rng = np.random.default_rng(71)
+    kv_len = [int(x) for x in rng.integers(1, cap + 1, size=batch)]
+    kv_len[:4] = [1, B, B + 1, cap]
+    q, k, v = synth.decode_inputs(batch, hq, hkv, cap, d, "bf16", seed=72)
+    kp, vp, table = to_pages(k, v, B, n_extra=7, seed=73)
+    for bi, n in enumerate(kv_len):
+        table[bi, (n - 1) // B + 1:] = -12345
+    lens = torch.tensor(kv_len, dtype=torch.int32).cuda()
+    qd = q.cuda()
+    o, lse = pa.decode_paged(pat, qd, kp.cuda(), vp.cuda(), table.cuda(), lens)
+    oc, lsec = pa.decode(pat, qd, k.cuda(), v.cuda(), lens)
+    torch.cuda.synchronize()
+    assert torch.equal(o, oc) and torch.equal(lse, lsec)
+    go, glse = o.double().cpu().numpy(), lse.double().cpu().numpy()
+    assert np.isfinite(go).all() and np.isfinite(glse).all()
+    oo, olse = orc.decode(synth.to_numpy_storage(q), synth.to_numpy_storage(k), synth.to_numpy_storage(v),
+                          np.asarray(kv_len), oracle_pattern(pat), None)
+    assert np.abs(go - oo).max() <= TOL_O["bf16"]
+    assert np.abs(glse - olse).max() <= TOL_LSE
