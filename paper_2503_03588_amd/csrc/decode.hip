@@ -27,6 +27,9 @@
 //    the whole merge.  Partials, counter and the merging loads act at device
 //    scope by themselves; no fence is used, because a device-scope fence writes
 //    back and invalidates a whole L2 on this chip.
+//  * With several work items per compute unit (large batches) persistent
+//    workgroups take over (pa_decode_stream_kernel): the loads of the next item
+//    are in flight while the current one is merged.
 #include <math.h>
 #include <atomic>
 #include "common.h"
