@@ -142,6 +142,8 @@ def test_back_to_back_calls_on_one_workspace():
     (64, 4, 1, 8, 4, 128, 2048, 288),      # 288 x 4 x 2 splits = 2304 work items on 256 compute units
     (128, 4, 1, 8, 2, 64, 4096, 200),      # two chunks per block, head_dim 64, three splits
     (64, 3, 2, 4, 4, 128, 1024, 300),      # one query head per KV head
+    (64, 4, 1, 8, 4, 128, 512, 300),       # rows of at most 8 chunks: one split, outputs written without a merge kernel
+    (64, 4, 1, 32, 2, 128, 1536, 260),     # 16 query heads per KV head: the largest LDS footprint
 ])
 def test_large_batches_on_persistent_workgroups(B, W, S, hq, hkv, d, cap, batch):
     # With at least four work items (sequence, KV head, split) per compute unit and every row a single pass, the
