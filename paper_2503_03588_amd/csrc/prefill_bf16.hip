@@ -351,19 +351,58 @@ void pa_prefill_bf16_kernel(bf16_params p) {
     for (int j = 0; j < LPT; ++j) fill_part(j);
   };
 
-  // ---- Q^T fragments: lane = query column, 8 consecutive d per 16-wide step ----
+  // ---- Q^T fragments: lane = query column.  The contraction index of S^T = K Q^T may be permuted freely as long
+  // as K and Q agree, and here 16-wide step c of lane half hh takes the d values 8(c + NC*hh) .. +7, so that a
+  // lane's fragments are the D contiguous bytes at D*hh of its row.  They are loaded quad-wise: in load m the four
+  // lanes of a quad read 64 contiguous bytes of ONE of the quad's four rows, and a 4x4 transpose inside the quad
+  // (q_arrange) then hands every lane the pieces of its own row.  Loading row-per-lane (every lane 16 bytes of
+  // its own row) costs the compute unit's address unit a cache-line look-up per lane: ~4 k cycles for the 64
+  // loads of a workgroup, queued at every item boundary in front of the tile copies and the output stores.
+  constexpr int QE = NC / 4;                 // 64-byte pieces per lane half of a row
+  u32x4 qraw[NC];
   bf16x8 qf[NC];
   auto load_q = [&](const item_t& it) {
     const int task = it.chunk * NW + wave;
     const bool act = task < p.tasks;
     const int g = act ? task / slices : 0, sl = act ? task % slices : 0;
-    const int64_t tok = (int64_t)it.i * p.B + sl * QW + ln;
-    const __bf16* qrow = p.q + (((int64_t)it.b * p.hq + it.kvh * p.G + g) * p.q_rows + (tok - p.q_start)) * D;
-    const bool ok = act && tok < p.N;
+    const int64_t tok0 = (int64_t)it.i * p.B + sl * QW + (ln & ~3);          // first row of this lane's quad
+    const __bf16* qbase = p.q + (((int64_t)it.b * p.hq + it.kvh * p.G + g) * p.q_rows + (tok0 - p.q_start)) * D
+                          + (D / 2) * hh + 8 * (lane & 3);
 #pragma unroll
-    for (int c = 0; c < NC; ++c) {
-      bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-      qf[c] = ok ? *reinterpret_cast<const bf16x8*>(qrow + 16 * c + 8 * hh) : z;
+    for (int m = 0; m < NC; ++m) {
+      const int rho = m / QE, e = m % QE;
+      const bool ok = act && tok0 + rho < p.N;
+      qraw[m] = ok ? *reinterpret_cast<const u32x4*>(qbase + (int64_t)rho * D + 32 * e) : u32x4{0, 0, 0, 0};
+    }
+  };
+  // qraw[rho*QE + e] of lane j (of its quad) is piece 4e + j of row rho; qf[4e + j'] of lane rho is that piece
+  auto q_arrange = [&]() {
+    const bool odd = lane & 1, upper = lane & 2;
+    auto quad_xor1 = [](uint32_t x) -> uint32_t { return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0xB1, 0xF, 0xF, true); };
+    auto quad_xor2 = [](uint32_t x) -> uint32_t { return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0x4E, 0xF, 0xF, true); };
+#pragma unroll
+    for (int e = 0; e < QE; ++e) {
+      uint32_t c[4][4];
+#pragma unroll
+      for (int rho = 0; rho < 4; ++rho)
+#pragma unroll
+        for (int w = 0; w < 4; ++w) c[rho][w] = qraw[rho * QE + e][w];
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        // stage 1: lanes i and i^1 trade c[k^1]; stage 2: lanes i and i^2 trade c[k^2] (all permutes evaluated
+        // before any select: a lane can only be read while it is active)
+        const uint32_t x0 = quad_xor1(c[0][w]), x1 = quad_xor1(c[1][w]), x2 = quad_xor1(c[2][w]), x3 = quad_xor1(c[3][w]);
+        const uint32_t a0 = odd ? x1 : c[0][w], a1 = odd ? c[1][w] : x0;
+        const uint32_t a2 = odd ? x3 : c[2][w], a3 = odd ? c[3][w] : x2;
+        const uint32_t y0 = quad_xor2(a0), y1 = quad_xor2(a1), y2 = quad_xor2(a2), y3 = quad_xor2(a3);
+        c[0][w] = upper ? y2 : a0; c[2][w] = upper ? a2 : y0;
+        c[1][w] = upper ? y3 : a1; c[3][w] = upper ? a3 : y1;
+      }
+#pragma unroll
+      for (int k2 = 0; k2 < 4; ++k2) {
+        const u32x4 v4 = {c[k2][0], c[k2][1], c[k2][2], c[k2][3]};
+        qf[4 * e + k2] = __builtin_bit_cast(bf16x8, v4);
+      }
     }
   };
 
@@ -386,9 +425,9 @@ void pa_prefill_bf16_kernel(bf16_params p) {
 
   // Per-lane LDS base addresses of the fragment reads: ka inside the stage whose K tile is multiplied next,
   // va inside the stage whose V tile is multiplied next; they are advanced in place from stage to stage.
-  // K fragment (d-step c, key half rt) of lane (ln, hh): row 32rt + ln, chunk 2c + hh.
-  constexpr int K_C = 32 * RPI, K_RT = (32 / RPI) * SRB;                 // offsets per d-step and per key half
-  const uint32_t ka0 = lds0 + (ln / RPI) * SRB + ((hh * RPI + ln % RPI) << 4);
+  // K fragment (d-step c, key half rt) of lane (ln, hh): row 32rt + ln, chunk c + NC*hh (as the Q fragments).
+  constexpr int K_C = 16 * RPI, K_RT = (32 / RPI) * SRB;                 // offsets per d-step and per key half
+  const uint32_t ka0 = lds0 + (ln / RPI) * SRB + ((hh * NC * RPI + ln % RPI) << 4);
   // V^T fragment (16-key step kk, d tile dt): two transposing reads, rows 16kk + r4 and 16kk + r4 + 8,
   // chunk 4dt + x, 8-byte half lane&1
   constexpr int V_KK = (16 / RPI) * SRB, V_DT = 4 * RPI * 16, V_HI = (8 / RPI) * SRB;
@@ -490,7 +529,8 @@ void pa_prefill_bf16_kernel(bf16_params p) {
     // makes the compiler wait for them here, once, instead of guarding each later use inside the loops
     // with a wait that would also drain the asynchronous copies.
 #pragma unroll
-    for (int c = 0; c < NC; ++c) asm volatile("" : "+v"(qf[c]));
+    for (int c = 0; c < NC; ++c) asm volatile("" : "+v"(qraw[c]));
+    q_arrange();
 
     // ---- look-ahead: the table of the next item from its prefetched list row (the first two tables were
     // built above), and the copy of the row of the item after it ----
@@ -650,12 +690,12 @@ void pa_prefill_bf16_kernel(bf16_params p) {
     for (; t + 1 < T1; t += 2) { step(t, std::false_type{}, Sc, Sd); step(t + 1, std::false_type{}, Sd, Sc); }
     for (; t < T1; ++t) { step(t, std::false_type{}, Sc, Sd); Sc[0] = Sd[0]; Sc[1] = Sd[1]; }
     for (; t < T2; ++t) { step(t, std::true_type{}, Sc, Sd); Sc[0] = Sd[0]; Sc[1] = Sd[1]; }
-    for (; t < n_my; ++t) {
-      // ---- last tile of this wavefront: the rest of P(t), O += P(t) V(t) ----
-      advance_k();
-      top(t);
-      fill_all();
-      if (more && t == n_steps - 1) load_q(it1);
+    // The rest of the item: this wavefront's last tile (t == n_my - 1), then idle iterations that only copy, up to
+    // n_steps in all.  The Q rows of the next item are requested in the item's last iteration, after its barrier,
+    // at ONE place in straight-line code: inside a loop, or at a second place, the compiler has to assume that
+    // earlier loads into the same registers are still under way and drains the whole memory queue first, the
+    // tile copies issued just before included (a trip to memory at every item boundary).
+    auto last_tile = [&]() {      // the rest of P(t), O += P(t) V(t)
       u32x4 Pk[4];
       Pk[0] = P0;
       float pe[32];
@@ -670,14 +710,29 @@ void pa_prefill_bf16_kernel(bf16_params p) {
         const int kk = (sl2 - 2 * NC) / ND, dt = (sl2 - 2 * NC) % ND;
         O[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(load_frag(sl2), __builtin_bit_cast(bf16x8, Pk[kk]), O[dt], 0, 0, 0);
       }
-      advance_v();
-    }
-    for (; t < n_steps; ++t) {
+    };
+    if (t < n_my && t + 1 < n_steps) {          // the last tile, with idle iterations to follow
       advance_k();
       top(t);
       fill_all();
-      if (more && t == n_steps - 1) load_q(it1);
+      last_tile();
       advance_v();
+      ++t;
+    }
+    for (; t + 1 < n_steps; ++t) {
+      advance_k();
+      top(t);
+      fill_all();
+      advance_v();
+    }
+    if (t < n_steps) {                          // the item's last iteration: the last tile or an idle one
+      advance_k();
+      top(t);
+      fill_all();
+      if (more) load_q(it1);
+      if (t < n_my) last_tile();
+      advance_v();
+      ++t;
     }
 
     // ---- epilogue ----
@@ -714,6 +769,10 @@ void pa_prefill_bf16_kernel(bf16_params p) {
       const bool odd = lane & 1, upper = lane & 2;
       auto quad_xor1 = [](uint32_t x) -> uint32_t { return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0xB1, 0xF, 0xF, true); };
       auto quad_xor2 = [](uint32_t x) -> uint32_t { return (uint32_t)__builtin_amdgcn_mov_dpp((int)x, 0x4E, 0xF, 0xF, true); };
+      // The next item's Q rows are waited for here, before the output stores go out: after them the same wait
+      // would also wait for the stores to be acknowledged (loads and stores share one counter).
+#pragma unroll
+      for (int c = 0; c < NC; ++c) asm volatile("" : "+v"(qraw[c]));
       const int li = lane & 3;
       const int64_t tok0 = tok - li;                   // first row of the quad
       __bf16* obase = p.o + (((int64_t)it.b * p.hq + h) * p.q_rows + (tok0 - p.q_start)) * D + hh * (D / 2) + 8 * li;
