@@ -157,6 +157,12 @@ void pa_prefill_bf16_kernel(bf16_params p) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform, and the compiler knows it
   const int ln = lane & 31, hh = lane >> 5;
   const int slices = p.B / QW;
+  // Which task of a work item this wavefront takes.  Wavefronts w and w+4 share a SIMD; the tasks of the lower
+  // half of a query block stop one diagonal tile before those of the upper half.  With four 32-query slices per
+  // head (blocks of 128 keys) tasks w and w+4 are the same slice of two heads, and whole SIMDs would idle in the
+  // item's last step while the others carry two wavefronts; the tasks are dealt so that every SIMD gets one
+  // wavefront of either kind (wavefront w: head (w>>1)&1, slice (w&1) + 2(w>>2)).
+  const int wtask = (NW == 8 && slices == 4) ? ((wave & 1) | (((wave >> 2) & 1) << 1) | (((wave >> 1) & 1) << 2)) : wave;
 
   // ---- this workgroup's work items: item k is number xcd*per_xcd + cuslot + nslots*k of the launch, so that
   // the workgroups of one XCD (one L2) work on neighbouring query blocks at any time ----
@@ -362,7 +368,7 @@ void pa_prefill_bf16_kernel(bf16_params p) {
   u32x4 qraw[NC];
   bf16x8 qf[NC];
   auto load_q = [&](const item_t& it) {
-    const int task = it.chunk * NW + wave;
+    const int task = it.chunk * NW + wtask;
     const bool act = task < p.tasks;
     const int g = act ? task / slices : 0, sl = act ? task % slices : 0;
     const int64_t tok0 = (int64_t)it.i * p.B + sl * QW + (ln & ~3);          // first row of this lane's quad
@@ -498,7 +504,7 @@ void pa_prefill_bf16_kernel(bf16_params p) {
   for (int k = 0; k < n_items; ++k) {
     const bool more = k + 1 < n_items;
     // ---- per-item geometry ----
-    const int task = it.chunk * NW + wave;
+    const int task = it.chunk * NW + wtask;
     const bool active = task < p.tasks;
     const int g = active ? task / slices : 0;
     const int sl = active ? task % slices : 0;
