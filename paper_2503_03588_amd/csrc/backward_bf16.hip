@@ -227,16 +227,25 @@ __global__ __launch_bounds__(64 * NW) void pa_bwd_dq_kernel(bwd_params p) {
   const int b = (int)(L / p.hkv);
 
   // ---- the row's tiles: every 64-key tile of every listed block up to the diagonal one ----
-  if (tid == 0) {
+  // The first wavefront reads 64 list entries at a time, one per lane (a single thread walking the list pays a
+  // trip to memory per entry, at the start of every workgroup); the rank of a valid entry is a prefix count.
+  if (wave == 0) {
     int n = p.kv_cnt[i];
     if (n > p.max_k) n = p.max_k;
-    int w = 0;
-    for (int e = 0; e < n; ++e) {
-      const int j = p.kv_idx[(int64_t)i * p.max_k + e];
-      if (j < 0 || j > i) continue;
-      for (int u = 0; u < p.subs && w < TILE_CAP; ++u) s_tile[w++] = j * p.B + u * KT;
+    n = __builtin_amdgcn_readfirstlane(n);
+    int blocks = 0;
+    for (int base = 0; base < n; base += 64) {
+      const int e = base + lane;
+      const int j = e < n ? p.kv_idx[(int64_t)i * p.max_k + e] : -1;
+      const bool valid = j >= 0 && j <= i;
+      const uint64_t vm = __builtin_amdgcn_ballot_w64(valid);
+      const int rank = blocks + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(vm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)vm, 0));
+      if (valid)
+        for (int u = 0; u < p.subs; ++u)
+          if (rank * p.subs + u < TILE_CAP) s_tile[rank * p.subs + u] = j * p.B + u * KT;
+      blocks += __builtin_popcountll(vm);
     }
-    s_ntiles = w;
+    if (lane == 0) s_ntiles = blocks * p.subs < TILE_CAP ? blocks * p.subs : TILE_CAP;
   }
   __syncthreads();
   const int n_tiles = s_ntiles;
@@ -248,6 +257,20 @@ __global__ __launch_bounds__(64 * NW) void pa_bwd_dq_kernel(bwd_params p) {
   const int64_t tok = (int64_t)i * p.B + sl * 32 + ln;          // this lane's query
   const bool ok = active && tok < p.N;
   const int64_t qrow = ((int64_t)b * p.hq + h) * p.N + (ok ? tok : 0);
+
+  const __bf16* kslab = p.k + ((int64_t)b * p.hkv + kvh) * p.N * D;
+  const __bf16* vslab = p.v + ((int64_t)b * p.hkv + kvh) * p.N * D;
+  static_assert(G::IPT % NW == 0, "tile copies must divide over the wavefronts");
+  constexpr int CPF = 2 * G::IPT / NW;     // copies per wavefront and fill (K and V)
+  auto fill = [&](int t) {
+    const int key0 = s_tile[t];
+    const uint32_t dst = lds0 + (t % NSTG) * STAGEB;
+    copy_tile<D, NW>(kslab, key0, p.N - 1, dst, wave, lane);
+    copy_tile<D, NW>(vslab, key0, p.N - 1, dst + G::TILEB, wave, lane);
+  };
+  // the first tiles are requested before this wavefront's own rows: their copies would queue behind those loads
+  for (int s0 = 0; s0 < NSTG - 1; ++s0)
+    if (s0 < n_tiles) fill(s0);
 
   bf16x8 qf[NC], dof[NC];
   reg_rows<D>(p.q + qrow * D, ok, lane, qf);
@@ -261,21 +284,10 @@ __global__ __launch_bounds__(64 * NW) void pa_bwd_dq_kernel(bwd_params p) {
   for (int dt = 0; dt < ND; ++dt)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[dt][r] = 0.f;
-
-  const __bf16* kslab = p.k + ((int64_t)b * p.hkv + kvh) * p.N * D;
-  const __bf16* vslab = p.v + ((int64_t)b * p.hkv + kvh) * p.N * D;
-  static_assert(G::IPT % NW == 0, "tile copies must divide over the wavefronts");
-  constexpr int CPF = 2 * G::IPT / NW;     // copies per wavefront and fill (K and V)
-  auto fill = [&](int t) {
-    const int key0 = s_tile[t];
-    const uint32_t dst = lds0 + (t % NSTG) * STAGEB;
-    copy_tile<D, NW>(kslab, key0, p.N - 1, dst, wave, lane);
-    copy_tile<D, NW>(vslab, key0, p.N - 1, dst + G::TILEB, wave, lane);
-  };
-  for (int s0 = 0; s0 < NSTG - 1; ++s0)
-    if (s0 < n_tiles) fill(s0);
   // Tile t has landed when only the fills of tiles t+1 .. t+NSTG-2 are outstanding (the counter retires in
-  // order; the loads of Q, dO above are older still).  Near the end, where fewer fills follow, wait for all.
+  // order).  Near the end, where fewer fills follow, wait for all.  (With two stages every wait is for all, the
+  // loads of Q and dO included.)
+  static_assert(NSTG == 2, "the row loads above are younger than the first fills: the waits must cover them");
   for (int t = 0; t < n_tiles; ++t) {
     if (t + NSTG - 1 <= n_tiles) wait_vmcnt<(NSTG - 2) * CPF>(); else wait_vmcnt<0>();
     __syncthreads();                       // tile t has landed for everybody; everybody is done with tile t-1
@@ -604,7 +616,6 @@ void pa_bwd_dkv_split_kernel(bwd_params p) {
   const int key32 = (int)key, n32 = (int)p.N;
   const int64_t krow = ((int64_t)b * p.hkv + kvh) * p.N + (kok ? key : 0);
   bf16x8 xf[NC];
-  reg_rows<D>((krole ? p.v : p.k) + krow * D, kok, lane, xf);
 
   f32x16 acc[ND];
 #pragma unroll
@@ -641,6 +652,8 @@ void pa_bwd_dkv_split_kernel(bwd_params p) {
   };
   static_assert(G::IPT % NW == 0, "tile copies must divide over the wavefronts");
   fill(0);
+  // (after the first tile's copies: they would queue behind these row-per-lane loads)
+  reg_rows<D>((krole ? p.v : p.k) + krow * D, kok, lane, xf);
   // iteration it: the P side works on tile it, the dS side on tile it-1
   for (int it = 0; it <= n_tiles; ++it) {
     wait_vmcnt<0>();
