@@ -24,6 +24,8 @@ pytestmark = pytest.mark.gpu
     (50, 64, 4, 1, 2, 1, 128, 1),       # shorter than one block
     (1024, 64, 0, 0, 4, 4, 128, 1),     # W = 0: pure power pattern
     (2048, 64, 4, 1, 16, 1, 64, 1),     # 16 heads per KV head: several workgroups per query block
+    (3000, 128, 3, 1, 6, 2, 128, 1),    # blocks of 128 keys with 3 heads per KV head: a half-empty second workgroup, ragged
+    (2500, 128, 2, 1, 2, 2, 128, 2),    # blocks of 128 keys without GQA: four wavefronts
 ])
 def test_shapes(n, B, W, S, hq, hkv, d, batch):
     check_prefill(pa.Pattern(B, W, S), batch, hq, hkv, n, d, "bf16", seed=21)
