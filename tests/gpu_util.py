@@ -35,6 +35,11 @@ def check_prefill(pat, batch, hq, hkv, n, d, dtype, seed, rows=None, scale=0.0, 
     """Element-by-element comparison (all rows, or the sampled `rows`) against the oracle.
     Returns (max abs error of o, max abs error of lse)."""
     q, k, v = synth.qkv(batch, hq, hkv, n, d, dtype, seed, std)
+    return check_prefill_tensors(pat, q, k, v, dtype, rows, scale)
+
+
+def check_prefill_tensors(pat, q, k, v, dtype, rows=None, scale=0.0):
+    """The same comparison on given CPU tensors q [b,Hq,N,D], k, v [b,Hkv,N,D]."""
     go, glse = gpu_prefill(pat, q, k, v, scale)
     assert np.isfinite(go).all() and np.isfinite(glse).all()
     qs, ks, vs = (synth.to_numpy_storage(t) for t in (q, k, v))

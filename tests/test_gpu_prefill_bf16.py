@@ -8,7 +8,7 @@ import torch
 
 from paper_2503_03588_amd import binding as pa
 from paper_2503_03588_amd import synth
-from gpu_util import check_prefill, gpu_prefill, sample_rows
+from gpu_util import check_prefill, check_prefill_tensors, gpu_prefill, sample_rows
 
 pytestmark = pytest.mark.gpu
 
@@ -41,6 +41,36 @@ def test_explicit_scale_and_small_std():
     check_prefill(pa.Pattern(64, 2, 1), 1, 4, 2, 1024, 128, "bf16", seed=25, scale=0.2)
     # the other reading of "N(0,1) scaled by 1/sqrt(128)": inputs themselves scaled
     check_prefill(pa.Pattern(64, 4, 1), 1, 4, 1, 2048, 128, "bf16", seed=26, std=1.0 / math.sqrt(128))
+
+
+@pytest.mark.parametrize("B,flags", [(64, pa.POWER), (128, pa.POWER), (128, pa.DENSE)])
+def test_peaked_rows(B, flags):
+    # Logits with a standard deviation of ~11 (softmax scale 1 on N(0,1) inputs): nearly one-hot rows whose largest
+    # score keeps growing by many units from tile to tile, so a running reference point of the exponentials has
+    # to be moved again and again (with N(0,1) logits the first tile's maximum is never exceeded by much).
+    # V is drawn with a standard deviation of 1/4: a one-hot row's output is a single V row, and bf16 outputs of
+    # magnitude 4 and more are a whole 1.6e-2 apart from their neighbours, which leaves no room inside 2e-2.
+    q, k, _ = synth.qkv(1, 4, 2, 3000, 128, "bf16", seed=30)
+    v = synth.gaussian((1, 2, 3000, 128), "bf16", seed=30 + 20011, std=0.25)
+    check_prefill_tensors(pa.Pattern(B, 4, 1, flags=flags), q, k, v, "bf16", scale=1.0)
+
+
+@pytest.mark.parametrize("rising", [True, False])
+def test_scores_that_rise_or_fall_along_the_sequence(rising):
+    # keys with a component along the queries' common direction that grows (or shrinks) linearly with the position:
+    # the scaled scores of a row span ~80 units, every later (earlier) tile dominating the ones before it
+    n, d, hq, hkv = 4096, 128, 4, 2
+    q, k, v = synth.qkv(1, hq, hkv, n, d, "f32", seed=31, std=0.3)
+    u = torch.full((d,), 1.0 / math.sqrt(d))
+    ramp = torch.arange(n, dtype=torch.float32) / n
+    if not rising:
+        ramp = 1.0 - ramp
+    q = (q + 30.0 * u).to(torch.bfloat16)
+    k = (k + 30.0 * ramp[:, None] * u).to(torch.bfloat16)
+    v = v.to(torch.bfloat16)           # (standard deviation 0.3: see test_peaked_rows)
+    check_prefill_tensors(pa.Pattern(128, 2, 1), q, k, v, "bf16")
+    q2, k2, v2 = (t[:, :, :2048].contiguous() for t in (q, k, v))
+    check_prefill_tensors(pa.Pattern(64, 4, 1, flags=pa.DENSE), q2, k2, v2, "bf16")
 
 
 def test_window_covering_everything_equals_dense_kernel():
