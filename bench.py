@@ -29,6 +29,9 @@ PEAK_HBM_GBS = 8000.0            # MI355X HBM3E peak
 # WRITE_SIZE runs scaled by a copy kernel of known size (profiles/prefill_bf16_128k_pmc.md).
 # read 4.33 GB + written 1.09 GB per launch.
 PREFILL_TRAFFIC_BYTES = 5.43e9
+# The same for one decode launch at the default workload (profiles/decode_b16_64k_pmc.md):
+# read 55.5 MB (the partials that the merging workgroups read back included) + written 0.79 MB.
+DECODE_TRAFFIC_BYTES = 56.3e6
 
 
 def main():
@@ -418,7 +421,7 @@ def main():
                    "in_step_us": round(decode_in_step_us, 2), "steps_timed": dec_iters,
                    "roofline": {"bound": "hbm", "kernel": "pa_decode_kernel (+ merge)", "achieved": round(decode_gbs, 1),
                                 "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(decode_gbs / PEAK_HBM_GBS, 4),
-                                "bytes_per_step": decode_bytes, "traffic": None},
+                                "bytes_per_step": decode_bytes, "traffic": DECODE_TRAFFIC_BYTES},
                    "paged_cache_by_batch": paged},
         "dense_baseline": dense,
         "paper_setting_b256_w5_s1": sweep,
