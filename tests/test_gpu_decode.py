@@ -42,6 +42,9 @@ def run_decode(pat, batch, hq, hkv, cap, d, kv_len, seed, scale=0.0, calls=1):
     (64, 4, 1, 16, 1, 128, 1024, [1000]),                         # GQA 16
     (64, 3, 1, 2, 2, 128, 2048, [2048, 1]),                       # no GQA
     (64, 0, 0, 4, 2, 128, 4096, [4096, 4033]),                    # W = 0
+    (192, 3, 1, 4, 2, 128, 2304, [2304, 1000, 193, 192]),         # a block size that is no power of two: three chunks per block
+    (512, 2, 1, 4, 1, 128, 4096, [4096, 513]),                    # eight chunks per block
+    (1024, 2, 1, 2, 1, 64, 4096, [4096, 3000]),                   # the largest block
 ])
 def test_shapes_and_lengths(B, W, S, hq, hkv, d, cap, kv_len):
     run_decode(pa.Pattern(B, W, S), len(kv_len), hq, hkv, cap, d, kv_len, seed=31, calls=2)

@@ -36,6 +36,7 @@ def to_pages(k, v, block, n_extra, seed):
     (128, 4, 1, 8, 2, 128, 4096, [4096, 129, 128, 127]),          # two 64-token chunks per page
     (256, 5, 1, 4, 2, 64, 8192, [8192, 5000, 300]),               # paper's block size; head_dim 64
     (64, 2, 0, 7, 1, 128, 3008, [3008, 2999, 777]),               # GQA 7, no sink
+    (192, 3, 1, 4, 2, 128, 2304, [2304, 1000, 193]),              # pages of 192 tokens: three chunks per page
 ])
 def test_paged_matches_oracle_and_contiguous(B, W, S, hq, hkv, d, cap, kv_len):
     pat = pa.Pattern(B, W, S)

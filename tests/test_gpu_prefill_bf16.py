@@ -26,6 +26,9 @@ pytestmark = pytest.mark.gpu
     (2048, 64, 4, 1, 16, 1, 64, 1),     # 16 heads per KV head: several workgroups per query block
     (3000, 128, 3, 1, 6, 2, 128, 1),    # blocks of 128 keys with 3 heads per KV head: a half-empty second workgroup, ragged
     (2500, 128, 2, 1, 2, 2, 128, 2),    # blocks of 128 keys without GQA: four wavefronts
+    (2000, 192, 2, 1, 4, 2, 128, 1),    # a block size that is no power of two: three tiles per block, six slices per head
+    (3000, 512, 2, 1, 2, 1, 128, 1),    # eight tiles per block
+    (2500, 1024, 1, 1, 2, 1, 64, 1),    # the largest block: 16 tiles, 64 tasks per item
 ])
 def test_shapes(n, B, W, S, hq, hkv, d, batch):
     check_prefill(pa.Pattern(B, W, S), batch, hq, hkv, n, d, "bf16", seed=21)

@@ -29,6 +29,7 @@ def caches_from(k, v, cap):
     (8192, 64, 4, 1, 16, 4, 128, 2, 8192, [0, 4096, 8192], pa.POWER),             # chained work items inside a chunk
     (2048, 64, 3, 1, 4, 2, 64, 1, 2048, [0, 1024, 2048], 0),                      # sliding window, head_dim 64
     (2048, 64, 1, 0, 4, 2, 128, 1, 4096, [0, 512, 2048], pa.DENSE),               # dense
+    (1900, 192, 2, 1, 4, 2, 128, 1, 2304, [0, 768, 1900], pa.POWER),              # blocks of 192 tokens
 ])
 def test_chunks_equal_whole_prefill(n, B, W, S, hq, hkv, d, batch, cap, cuts, flags):
     pat = pa.Pattern(B, W, S, flags)

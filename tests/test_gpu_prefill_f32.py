@@ -27,6 +27,8 @@ def test_config1_tiny_prefill(sink):
     (1536, 256, 1, 0, 3, 3, 64, 1),     # four key tiles per block, pure power pattern
     (50, 64, 4, 1, 2, 2, 64, 1),        # shorter than one block
     (1024, 64, 0, 0, 2, 2, 64, 1),      # W = 0
+    (500, 48, 2, 1, 2, 1, 64, 1),       # blocks of three 16-key tiles
+    (1000, 192, 2, 1, 2, 1, 64, 1),     # blocks of three 64-key tiles
 ])
 def test_shapes(n, B, W, S, hq, hkv, d, batch):
     check_prefill(pa.Pattern(B, W, S), batch, hq, hkv, n, d, "f32", seed=11)
