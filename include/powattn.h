@@ -116,7 +116,7 @@ int powattn_mask_build(const powattn_pattern* pattern, int64_t seq_len,
  *   lse            device float [batch, n_q_heads, seq_len] or NULL:
  *                  natural-log sum of exp(scaled logits) over the attended keys
  *   dtype          POWATTN_BF16 (MFMA path, fp32 accumulation; head_dim 64 or 128,
- *                  block a multiple of 64) or POWATTN_F32 (plain FMA path;
+ *                  block a multiple of 64, at most 1024) or POWATTN_F32 (plain FMA path;
  *                  head_dim 64 or 128, block 16..256 and a multiple of 16)
  *   softmax_scale  logit scale; <= 0 selects 1/sqrt(head_dim) (Equation 1)
  * seq_len need not be a multiple of the block size.
@@ -144,7 +144,7 @@ int powattn_prefill(const powattn_pattern* pattern,
  *   k_cache, v_cache  device [batch, n_kv_heads, cache_capacity, head_dim]
  *   lse            device float [batch, n_q_heads, q_len] or NULL
  *   q_start        a multiple of pattern->block; q_start + q_len <= cache_capacity
- *   dtype          POWATTN_BF16 only; head_dim 64 or 128; block a multiple of 64
+ *   dtype          POWATTN_BF16 only; head_dim 64 or 128; block a multiple of 64, at most 1024
  * Errors: INVALID_ARG, UNSUPPORTED, HIP_ERROR.
  */
 int powattn_prefill_chunk(const powattn_pattern* pattern,
@@ -167,7 +167,7 @@ int powattn_prefill_chunk(const powattn_pattern* pattern,
  *   lse            device float [batch, n_q_heads, padded_len] or NULL
  *   h_seq_len      HOST int64 [batch], 0 <= h_seq_len[b] <= padded_len (0: nothing to do)
  *   d_kv_cnt, d_kv_idx, max_k   lists covering at least ceil(max_b h_seq_len[b] / block) rows
- *   dtype          POWATTN_BF16 only; head_dim 64 or 128; block a multiple of 64
+ *   dtype          POWATTN_BF16 only; head_dim 64 or 128; block a multiple of 64, at most 1024
  * Errors: INVALID_ARG, UNSUPPORTED, HIP_ERROR.
  */
 int powattn_prefill_varlen(const powattn_pattern* pattern,
@@ -199,7 +199,7 @@ size_t powattn_decode_workspace_bytes(const powattn_pattern* pattern, int32_t ba
  *   d_kv_len       device int32 [batch], 1 <= kv_len[b] <= cache_capacity
  *                  (values outside that range are clamped into it by the kernel)
  *   lse            device float [batch, n_q_heads] or NULL
- *   dtype          POWATTN_BF16 only; head_dim 64 or 128; block a multiple of 64
+ *   dtype          POWATTN_BF16 only; head_dim 64 or 128; block a multiple of 64, at most 1024
  *   workspace      device, at least powattn_decode_workspace_bytes(...) bytes,
  *                  256-byte aligned; contents on entry are ignored.  Two calls
  *                  that may run at the same time must not share a workspace,
