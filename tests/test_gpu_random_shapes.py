@@ -1,0 +1,72 @@
+"""GPU parity on seeded random shapes: prefill (bf16 and fp32), decode and the gradients against the oracle, with
+block sizes, windows, sinks, flags, head groupings, head_dims, batch sizes and lengths drawn at random inside what
+the entry points accept (small enough for the dense float64 oracle).  The hand-picked cases of the other files
+name the situations they are meant to hit; this one looks for the ones nobody thought of.  Bars as there."""
+import random
+
+import pytest
+
+from paper_2503_03588_amd import binding as pa
+from gpu_util import check_prefill
+from test_gpu_backward import run_backward
+from test_gpu_decode import run_decode
+
+pytestmark = pytest.mark.gpu
+
+
+def draw_cases(seed, count):
+    rng = random.Random(seed)
+    cases = []
+    for c in range(count):
+        kind = rng.choice(["prefill_bf16", "prefill_bf16", "prefill_f32", "decode", "backward"])
+        hkv = rng.choice([1, 1, 2, 3, 4])
+        hq = hkv * rng.choice([1, 2, 3, 4, 5, 7, 8, 16])
+        d = rng.choice([64, 128])
+        W = rng.choice([0, 1, 2, 3, 4, 5, 8])
+        S = rng.choice([0, 1, 1, 2])
+        flags = rng.choice([pa.POWER, pa.POWER, pa.POWER, 0, pa.DENSE])
+        if kind in ("decode", "backward"):
+            flags &= ~pa.DENSE                     # these two take the pattern's own rows only
+        if not (flags & (pa.POWER | pa.DENSE)) and W < 1:
+            W = 1                                  # a sliding window needs at least the diagonal block
+        if kind == "prefill_bf16":
+            B = rng.choice([64, 64, 128, 128, 192, 256, 320, 512])
+            n = rng.randint(1, 2600)
+            batch = rng.choice([1, 1, 2])
+            if hq * batch * n > 40000:             # keep the oracle's N x N matrices per head few
+                hq, hkv = rng.choice([(4, 1), (4, 2), (6, 2), (7, 1)])
+            cases.append((kind, dict(B=B, W=W, S=S, flags=flags, hq=hq, hkv=hkv, d=d, n=n, batch=batch, seed=1000 + c)))
+        elif kind == "prefill_f32":
+            B = rng.choice([16, 32, 48, 64, 80, 128, 256])
+            hq, hkv = rng.choice([(2, 1), (2, 2), (4, 2), (3, 1)])
+            cases.append((kind, dict(B=B, W=W, S=S, flags=flags, hq=hq, hkv=hkv, d=d, n=rng.randint(1, 900), batch=1,
+                                     seed=2000 + c)))
+        elif kind == "decode":
+            B = rng.choice([64, 64, 128, 192, 256, 512])
+            cap = rng.randint(1, 6000)
+            lens = [cap] + [rng.randint(1, cap) for _ in range(rng.choice([0, 1, 2, 4]))]
+            cases.append((kind, dict(B=B, W=W, S=S, flags=flags, hq=hq, hkv=hkv, d=d, cap=cap, lens=lens,
+                                     calls=rng.choice([1, 2]), seed=3000 + c)))
+        else:
+            B = rng.choice([64, 128, 256])
+            hq, hkv = rng.choice([(2, 1), (2, 2), (4, 2), (6, 2), (4, 1), (8, 1)])
+            cases.append((kind, dict(B=B, W=W, S=S, flags=flags, hq=hq, hkv=hkv, d=d, n=rng.randint(1, 1100),
+                                     seed=4000 + c)))
+    return cases
+
+
+CASES = draw_cases(20250303, 48)
+
+
+@pytest.mark.parametrize("kind,c", CASES, ids=[f"{i}-{k}" for i, (k, _) in enumerate(CASES)])
+def test_random_shape(kind, c):
+    print(kind, c, flush=True)
+    pat = pa.Pattern(c["B"], c["W"], c["S"], c["flags"])
+    if kind == "prefill_bf16":
+        check_prefill(pat, c["batch"], c["hq"], c["hkv"], c["n"], c["d"], "bf16", seed=c["seed"])
+    elif kind == "prefill_f32":
+        check_prefill(pat, c["batch"], c["hq"], c["hkv"], c["n"], c["d"], "f32", seed=c["seed"])
+    elif kind == "decode":
+        run_decode(pat, len(c["lens"]), c["hq"], c["hkv"], c["cap"], c["d"], c["lens"], seed=c["seed"], calls=c["calls"])
+    else:
+        run_backward(pat, 1, c["hq"], c["hkv"], c["n"], c["d"], seed=c["seed"])
