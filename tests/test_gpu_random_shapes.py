@@ -1,6 +1,7 @@
 """GPU parity on seeded random shapes: prefill (bf16 and fp32), decode and the gradients against the oracle, with
 block sizes, windows, sinks, flags, head groupings, head_dims, batch sizes and lengths drawn at random inside what
-the entry points accept (small enough for the dense float64 oracle).  The hand-picked cases of the other files
+the entry points accept (small enough for the dense float64 oracle); then the chunked, padded-batch and paged entry
+points on random shapes through the checks of their own test files.  The hand-picked cases of the other files
 name the situations they are meant to hit; this one looks for the ones nobody thought of.  Bars as there."""
 import random
 
@@ -10,6 +11,9 @@ from paper_2503_03588_amd import binding as pa
 from gpu_util import check_prefill
 from test_gpu_backward import run_backward
 from test_gpu_decode import run_decode
+from test_gpu_decode_paged import test_paged_matches_oracle_and_contiguous as check_paged
+from test_gpu_prefill_chunk import test_chunks_equal_whole_prefill as check_chunks
+from test_gpu_prefill_varlen import test_padded_batch as check_padded_batch
 
 pytestmark = pytest.mark.gpu
 
@@ -70,3 +74,49 @@ def test_random_shape(kind, c):
         run_decode(pat, len(c["lens"]), c["hq"], c["hkv"], c["cap"], c["d"], c["lens"], seed=c["seed"], calls=c["calls"])
     else:
         run_backward(pat, 1, c["hq"], c["hkv"], c["n"], c["d"], seed=c["seed"])
+
+
+def draw_serving_cases(seed, count):
+    rng = random.Random(seed)
+    cases = []
+    for c in range(count):
+        kind = rng.choice(["chunk", "varlen", "paged"])
+        hkv = rng.choice([1, 2, 4])
+        hq = hkv * rng.choice([1, 2, 4, 7])
+        d = rng.choice([64, 128])
+        W = rng.choice([0, 1, 2, 4, 5])
+        S = rng.choice([0, 1, 2])
+        B = rng.choice([64, 64, 128, 192, 256])
+        if kind == "chunk":
+            flags = rng.choice([pa.POWER, pa.POWER, 0, pa.DENSE])
+            if not (flags & (pa.POWER | pa.DENSE)) and W < 1:
+                W = 1
+            nb = rng.randint(1, max(1, 2400 // B))
+            n = nb * B - rng.randint(0, B - 1)
+            cap = n + rng.randint(0, 300)
+            inner = sorted(set(rng.randint(1, nb) * B for _ in range(rng.randint(0, 3))))
+            cuts = [0] + [x for x in inner if x < n] + [n]          # chunks start at block boundaries
+            batch = rng.choice([1, 2])
+            if hq * batch * n > 30000:
+                hq, hkv = 4, 2
+            cases.append((kind, (n, B, W, S, hq, hkv, d, batch, cap, cuts, flags)))
+        elif kind == "varlen":
+            npad = rng.randint(1, 1500)
+            lens = [rng.choice([0, npad, rng.randint(0, npad)]) for _ in range(rng.randint(1, 4))]
+            if hq * len(lens) * npad > 30000:
+                hq, hkv = 4, 2
+            cases.append((kind, (B, W, S, hq, hkv, d, npad, lens)))
+        else:
+            cap = rng.randint(1, max(1, 5000 // B)) * B             # whole pages
+            lens = [cap] + [rng.randint(1, cap) for _ in range(rng.randint(0, 3))]
+            cases.append((kind, (B, W, S, hq, hkv, d, cap, lens)))
+    return cases
+
+
+SERVING_CASES = draw_serving_cases(20250304, 24)
+
+
+@pytest.mark.parametrize("kind,args", SERVING_CASES, ids=[f"{i}-{k}" for i, (k, _) in enumerate(SERVING_CASES)])
+def test_random_serving_shape(kind, args):
+    print(kind, args, flush=True)
+    {"chunk": check_chunks, "varlen": check_padded_batch, "paged": check_paged}[kind](*args)
