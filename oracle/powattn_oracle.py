@@ -29,8 +29,7 @@ import numpy as np
 @dataclass(frozen=True)
 class Pattern:
     """Hyper-parameters of the static pattern (Algorithm 1's B and W, plus the
-    sink width that Algorithm 1 fixes at one block and Section 4.1 calls
-    "1 block of initial tokens").
+    sink width, which Algorithm 1 and the setting of Section 4.1 fix at one block).
 
     block  : B, tokens per block
     window : W, block distances 0..W-1 are attended
@@ -50,25 +49,27 @@ class Pattern:
 # Algorithm 1: the mask predicate
 # --------------------------------------------------------------------------
 def attended(q_idx, kv_idx, pat: Pattern):
-    """Algorithm 1, for integer arrays q_idx and kv_idx that broadcast together.
+    """The attended set of Algorithm 1, for integer arrays q_idx and kv_idx that broadcast together.
 
-    blk = floor(q/B) - floor(kv/B); a pair is attended when it is causal and
-    the block distance is inside the window, or has at most one bit set
-    (blk & (blk-1) == 0, which also admits blk == 0), or the key lies in the
-    sink blocks.
+    With d = floor(q/B) - floor(kv/B) the block distance, the set is
+        causal  and  ( window  or  power  or  sink )
+    where causal = {kv <= q}, window = {d < W}, sink = {key inside the first S
+    blocks} and power = {d is zero or a power of two}, i.e. the binary form of
+    d has at most one digit set (counted directly here: a non-causal pair has
+    d < 0 at worst and is excluded by the causal term whatever the other terms
+    say, so d is clipped at zero before counting).
     """
     q_idx = np.asarray(q_idx, dtype=np.int64)
     kv_idx = np.asarray(kv_idx, dtype=np.int64)
-    causal = q_idx >= kv_idx
+    causal = kv_idx <= q_idx
     if pat.dense:
         return causal
-    blk = q_idx // pat.block - kv_idx // pat.block
-    m_window = blk < pat.window
-    m_sink = kv_idx < pat.sink * pat.block
-    allowed = m_window | m_sink
+    q_blk, kv_blk = q_idx // pat.block, kv_idx // pat.block
+    d = q_blk - kv_blk
+    members = (d < pat.window) | (kv_blk < pat.sink)
     if pat.power:
-        allowed = allowed | ((blk & (blk - 1)) == 0)
-    return causal & allowed
+        members = members | (np.bitwise_count(np.maximum(d, 0)) <= 1)
+    return causal & members
 
 
 def token_mask(seq_len: int, pat: Pattern):
@@ -346,9 +347,9 @@ def column_lists(seq_len: int, pat: Pattern):
 
 
 # --------------------------------------------------------------------------
-# Work counts used by the bench's FLOP accounting
+# Work count: the bench's CPU-baseline leg checks the library's own count of
+# attended block pairs (the basis of its FLOP figure) against this one
 # --------------------------------------------------------------------------
 def attended_pairs(seq_len: int, pat: Pattern) -> int:
-    """Sum over query blocks of the number of attended key blocks."""
-    cnt, _, _ = block_lists(seq_len, pat)
-    return int(cnt.sum())
+    """Number of (query block, key block) pairs with at least one attended token pair."""
+    return int(block_mask(seq_len, pat).sum())

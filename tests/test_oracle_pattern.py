@@ -206,9 +206,27 @@ def test_config_counts_and_invariants(cfg):
             assert set(range(max(0, i - W + 1), i + 1)) <= set(row.tolist())   # window complete
             for j in row:
                 assert i - j < W or j < S or _popcount(i - j) == 1
-        if nb <= 512:
-            depth = orc.reach_depth(orc.block_mask(n, pat))
-            assert depth.max() == dep
+        # multi-layer coverage (Section 3.1, Appendix A, Theorem B.1): the worst pair needs `dep` layers, which
+        # stays within ceil(log2 nb) and far below the 28 layers of the layer-stack configuration
+        depth = orc.reach_depth(orc.block_mask(n, pat))
+        assert depth.max() == dep
+        assert dep <= math.ceil(math.log2(nb)) <= 28
+        # the library-facing work count equals the set-union count
+        assert orc.attended_pairs(n, pat) == pairs
+
+
+@pytest.mark.parametrize("n,B,W,S,power", [(96, 4, 2, 1, True), (101, 4, 3, 0, True), (130, 16, 2, 2, False),
+                                           (64, 1, 1, 0, True), (7, 16, 4, 1, True)])
+def test_attended_pairs_counts_nonempty_blocks_of_the_token_mask(n, B, W, S, power):
+    # brute force on small sequences: count block pairs holding at least one attended token pair, one token
+    # pair at a time with the independent predicate above (also with a ragged last block)
+    pat = Pattern(block=B, window=W, sink=S, power=power)
+    nb = -(-n // B)
+    want = sum(any(brute_pair(q, kv, B, W, S, power)
+                   for q in range(i * B, min((i + 1) * B, n)) for kv in range(j * B, min((j + 1) * B, n)))
+               for i in range(nb) for j in range(nb))
+    assert orc.attended_pairs(n, pat) == want
+    assert orc.attended_pairs(n, Pattern(block=B, window=W, dense=True)) == nb * (nb + 1) // 2
 
 
 def test_decode_row_of_config_four():
