@@ -36,7 +36,7 @@ extern "C" {
 #define POWATTN_HIP_ERROR            4  /* the HIP runtime refused a launch; see powattn_strerror */
 
 /* powattn_pattern.flags */
-#define POWATTN_POWER  1u  /* attend block distances with exactly one bit set (Algorithm 1, "mask_power") */
+#define POWATTN_POWER  1u  /* attend block distances that are zero or a power of two (the power term of Algorithm 1) */
 #define POWATTN_DENSE  2u  /* full causal attention, A_i = {j <= i} (Section 3.1); other fields except block are ignored */
 
 /* element types of Q/K/V/O */
@@ -45,12 +45,13 @@ extern "C" {
 
 /*
  * The pattern's hyper-parameters, in the notation of Algorithm 1 (Section 3.3).
- * With blk = floor(q_idx/B) - floor(kv_idx/B), token q_idx attends token kv_idx
- * when  q_idx >= kv_idx  and  ( blk < W  or  blk & (blk-1) == 0  or
- * kv_idx < S*B ).  Algorithm 1 has S = 1; Section 4.1 uses B = 256, W = 5, S = 1.
- * The power-of-two test also admits blk == 0, so with POWATTN_POWER the diagonal
- * block is attended even when W == 0.  Without POWATTN_POWER (sliding window +
- * sink, the first baseline of Section 4.1) W must be >= 1.
+ * With d = floor(q/B) - floor(kv/B) the distance in blocks, query token q attends
+ * key token kv when kv <= q and at least one of: d < W (local window), d is zero
+ * or a power of two (POWATTN_POWER), kv lies in the first S blocks (sink).
+ * Algorithm 1 has S = 1; Section 4.1 uses B = 256, W = 5, S = 1.  Because the
+ * power term admits d == 0, the diagonal block is attended even when W == 0.
+ * Without POWATTN_POWER (sliding window + sink, the first baseline of
+ * Section 4.1) W must be >= 1.
  */
 typedef struct {
   int32_t block;   /* B: tokens per block, >= 1 */
@@ -188,8 +189,8 @@ size_t powattn_decode_workspace_bytes(const powattn_pattern* pattern, int32_t ba
 
 /*
  * Decode: one new token per sequence attends its KV cache under the same
- * pattern as prefill (Section 4.1: "consistent patterns during both prefilling
- * and decoding").  The cache already holds the new token's key and value, so
+ * pattern as prefill (Section 4.1 keeps one pattern for both phases).  The
+ * cache already holds the new token's key and value, so
  * the query of sequence b sits at position t = kv_len[b] - 1 and the result
  * equals row t of powattn_prefill over the first kv_len[b] cache positions.
  * The attended block list of row floor(t / B) is generated inside the kernel;

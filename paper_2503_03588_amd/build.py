@@ -20,6 +20,9 @@ ARCH = "gfx950"
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "-fPIC", f"--offload-arch={ARCH}",
     "-Wall", "-Wno-unused-function",
+    # the asynchronous-copy helpers name M0 as clobbered; the compiler notes that it is a reserved register
+    # (one it never hands out itself), which is the point of naming it
+    "-Wno-inline-asm",
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     # the prefill step is one fully unrolled instruction stream of 32 matrix instructions; the default size
@@ -71,5 +74,26 @@ def build(verbose: bool = True, extra_flags=()) -> str:
     return OUT
 
 
+def build_microbench(verbose: bool = True):
+    """The two machine micro-benchmarks (stand-alone executables that bench.py runs for its `measured_peaks`)."""
+    mdir = os.path.join(HERE, "microbench")
+    bdir = os.path.join(mdir, "bin")
+    os.makedirs(bdir, exist_ok=True)
+    outs = []
+    for name in ("mfma_peak", "stream_decode"):
+        out = os.path.join(bdir, name)
+        cmd = [hipcc(), "-O3", "-std=c++17", f"--offload-arch={ARCH}", "-Wno-unused-value", "-Wno-unused-result",
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               os.path.join(mdir, name + ".hip"), "-o", out]
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError(f"hipcc failed for {name}:\n{res.stdout}\n{res.stderr}")
+        outs.append(out)
+    if verbose:
+        print(f"built {len(outs)} micro-benchmarks in {bdir}")
+    return outs
+
+
 if __name__ == "__main__":
     build()
+    build_microbench()

@@ -13,6 +13,31 @@ int pa_note_hip(hipError_t e) {
   return POWATTN_HIP_ERROR;
 }
 
+void pa_current_device(int* dev_out, int* n_cu_out) {
+  static std::atomic<int> n_cu[64];     // zero-initialised; 0 = not looked up yet
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
+  int v = n_cu[dev].load(std::memory_order_relaxed);
+  if (v == 0) {                         // two threads may both look it up: they store the same value
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1) v = 1;
+    n_cu[dev].store(v, std::memory_order_relaxed);
+  }
+  if (dev_out) *dev_out = dev;
+  if (n_cu_out) *n_cu_out = v;
+}
+
+int pa_allow_dynamic_lds(const void* kernel, size_t bytes, std::atomic<unsigned long long>& done) {
+  int dev = 0;
+  pa_current_device(&dev, nullptr);
+  const unsigned long long bit = 1ull << dev;
+  if (done.load(std::memory_order_acquire) & bit) return POWATTN_OK;
+  // setting the limit twice is harmless, so threads that race here simply both set it
+  hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e != hipSuccess) return pa_note_hip(e);
+  done.fetch_or(bit, std::memory_order_release);
+  return POWATTN_OK;
+}
+
 int pa_check_pattern(const powattn_pattern* p) {
   if (!p) return POWATTN_INVALID_ARG;
   if (p->block < 1 || p->window < 0 || p->sink < 0) return POWATTN_INVALID_ARG;

@@ -66,11 +66,11 @@ __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
 __device__ __forceinline__ void async_copy16(const void* sbase, uint32_t voff, uint32_t lds_off) {
-  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_off) : "memory");
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_off) : "memory", "m0");
 }
 // one dword per lane: lane l's value lands at lds_off + 4*l
 __device__ __forceinline__ void async_copy4(const void* addr, uint32_t lds_off) {
-  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" ::"v"(addr), "s"(lds_off) : "memory");
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" ::"v"(addr), "s"(lds_off) : "memory", "m0");
 }
 template <typename T>
 __device__ __forceinline__ const T* uniform_ptr(const T* ptr) {
@@ -768,26 +768,16 @@ __global__ __launch_bounds__(256) void pa_bwd_sink_store_kernel(bwd_params p, in
 template <int D, int NW>
 int launch_dq(const bwd_params& p, int64_t items, hipStream_t stream) {
   constexpr size_t lds = NSTG * 2 * (size_t)tile_geo<D>::TILEB;
-  static bool done = false;
-  if (!done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pa_bwd_dq_kernel<D, NW>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return pa_note_hip(e);
-    done = true;
-  }
+  static std::atomic<unsigned long long> done{0};
+  if (int st = pa_allow_dynamic_lds(reinterpret_cast<const void*>(&pa_bwd_dq_kernel<D, NW>), lds, done)) return st;
   hipLaunchKernelGGL((pa_bwd_dq_kernel<D, NW>), dim3((uint32_t)items), dim3(64 * NW), lds, stream, p);
   return pa_note_hip(hipGetLastError());
 }
 template <int D, int NW>
 int launch_dkv(const bwd_params& p, dim3 grid, hipStream_t stream) {
   constexpr size_t lds = NSTG * (2 * (size_t)tile_geo<D>::TILEB + 512);
-  static bool done = false;
-  if (!done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pa_bwd_dkv_kernel<D, NW>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return pa_note_hip(e);
-    done = true;
-  }
+  static std::atomic<unsigned long long> done{0};
+  if (int st = pa_allow_dynamic_lds(reinterpret_cast<const void*>(&pa_bwd_dkv_kernel<D, NW>), lds, done)) return st;
   hipLaunchKernelGGL((pa_bwd_dkv_kernel<D, NW>), grid, dim3(64 * NW), lds, stream, p);
   return pa_note_hip(hipGetLastError());
 }
@@ -795,13 +785,8 @@ int launch_dkv(const bwd_params& p, dim3 grid, hipStream_t stream) {
 template <int D, int NSL>
 int launch_dkv_split(const bwd_params& p, dim3 grid, hipStream_t stream) {
   constexpr size_t lds = 3 * (2 * (size_t)tile_geo<D>::TILEB + 512) + 2 * (size_t)NSL * 4096;
-  static bool done = false;
-  if (!done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pa_bwd_dkv_split_kernel<D, NSL>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return pa_note_hip(e);
-    done = true;
-  }
+  static std::atomic<unsigned long long> done{0};
+  if (int st = pa_allow_dynamic_lds(reinterpret_cast<const void*>(&pa_bwd_dkv_split_kernel<D, NSL>), lds, done)) return st;
   hipLaunchKernelGGL((pa_bwd_dkv_split_kernel<D, NSL>), grid, dim3(128 * NSL), lds, stream, p);
   return pa_note_hip(hipGetLastError());
 }

@@ -11,6 +11,14 @@
 int pa_note_hip(hipError_t e);
 int pa_check_pattern(const powattn_pattern* p);
 
+// One-time, per-device launch set-up shared by the launchers; safe to call from several host threads.
+// pa_current_device: the current device (clamped to [0, 64)) and its number of compute units (cached).
+// pa_allow_dynamic_lds: raises a kernel's dynamic shared memory limit to `bytes` once per device; `done` is the
+// caller's file-scope mask of the devices on which it has been raised (bit = device).  Returns a status.
+#include <atomic>
+void pa_current_device(int* dev, int* n_cu);
+int pa_allow_dynamic_lds(const void* kernel, size_t bytes, std::atomic<unsigned long long>& done);
+
 struct pa_prefill_args {
   powattn_pattern pat;
   const int32_t* kv_cnt;

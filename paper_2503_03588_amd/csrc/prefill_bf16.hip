@@ -102,14 +102,14 @@ constexpr int TILE_CAP = 4096;   // tiles per query block with an explicit list 
 // Asynchronous 16-byte-per-lane copy global -> LDS: lane l's data lands at lds_off + 16*l.
 // Written as inline assembly on purpose: the compiler then does not pair every later LDS read
 // with a full vmcnt(0) wait, and the waits are placed by hand (wait_vmcnt below).  M0 carries
-// the LDS offset; nothing else in this kernel uses M0.
+// the LDS offset and is declared as clobbered.
 __device__ __forceinline__ void async_copy16(const void* sbase, uint32_t voff, uint32_t lds_off) {
-  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_off) : "memory");
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_off) : "memory", "m0");
 }
 // the same with the LDS offset given as a scalar base plus a constant
 template <int OFF>
 __device__ __forceinline__ void async_copy16_at(const void* sbase, uint32_t voff, uint32_t lds_base) {
-  asm volatile("s_add_u32 m0, %2, %3\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_base), "n"(OFF) : "memory", "scc");
+  asm volatile("s_add_u32 m0, %2, %3\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_base), "n"(OFF) : "memory", "scc", "m0");
 }
 
 // a wavefront-uniform pointer, forced into scalar registers
@@ -265,7 +265,7 @@ void pa_prefill_bf16_kernel(bf16_params p) {
       src = lane == 63 ? p.kv_cnt + it.i : p.kv_idx + (int64_t)it.i * p.max_k + e;
     }
     const uint32_t dst = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int*)&s_raw[0][0] + wave * 256;
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" ::"v"(src), "s"(__builtin_amdgcn_readfirstlane(dst)) : "memory");
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dword %0, off" ::"v"(src), "s"(__builtin_amdgcn_readfirstlane(dst)) : "memory", "m0");
   };
 
   // ---- asynchronous tile copy: this wavefront's share of the tile starting at key0 into a ring stage ----
@@ -821,26 +821,17 @@ void pa_prefill_bf16_kernel(bf16_params p) {
 template <int D, int NW, int NS, bool DENSE, bool CHAIN>
 int launch_as(const bf16_params& p, hipStream_t stream) {
   constexpr size_t lds = (size_t)NS * 2 * (KT / (512 / D)) * (1024 + 16 * (512 / D));
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&pa_prefill_bf16_kernel<D, NW, NS, DENSE, CHAIN>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (e != hipSuccess) return pa_note_hip(e);
-    attr_done = true;
-  }
+  static std::atomic<unsigned long long> attr_done{0};
+  if (int st = pa_allow_dynamic_lds(reinterpret_cast<const void*>(&pa_prefill_bf16_kernel<D, NW, NS, DENSE, CHAIN>), lds, attr_done))
+    return st;
   // One workgroup per work item, or, when the items can be chained (the block lists are short enough for the
   // look-ahead tables and registers), one persistent workgroup per compute unit that walks through its share.
   int64_t grid = (int64_t)p.per_xcd * 8;
   if (CHAIN) {
-    static int n_cu[64] = {0};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
-    if (n_cu[dev] == 0) {
-      int v = 0;
-      if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 8) v = 8;
-      n_cu[dev] = v;
-    }
-    const int64_t persistent = (int64_t)(n_cu[dev] / 8) * 8;
+    int n_cu = 0;
+    pa_current_device(nullptr, &n_cu);
+    if (n_cu < 8) n_cu = 8;
+    const int64_t persistent = (int64_t)(n_cu / 8) * 8;
     if (grid > persistent) grid = persistent;
   }
   hipLaunchKernelGGL((pa_prefill_bf16_kernel<D, NW, NS, DENSE, CHAIN>), dim3((uint32_t)grid), dim3(64 * NW), lds, stream, p);

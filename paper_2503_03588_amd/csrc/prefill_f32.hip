@@ -111,7 +111,7 @@ __global__ __launch_bounds__(4 * KT) void pa_prefill_f32_kernel(f32_params p) {
   }
 
   if (row_ok) {
-    const float inv = 1.0f / l_run;
+    const float inv = l_run > 0.f ? 1.0f / l_run : 0.f;    // a row whose list is empty: o = 0, lse = -inf
     float4* o4 = reinterpret_cast<float4*>(p.o + (((int64_t)b * p.hq + h) * p.N + qrow) * D);
 #pragma unroll
     for (int m = 0; m < NCH; ++m)

@@ -1,3 +1,6 @@
+// Sustained rate of back-to-back bf16 matrix instructions on this machine: the practical ceiling under the
+// published matrix peak (the shader clock under matrix load sits below the nominal one).  Built by
+// paper_2503_03588_amd/build.py; bench.py runs it and reports the best line as `measured_peaks.mfma_bf16_tflops`.
 #include <hip/hip_runtime.h>
 #include <stdio.h>
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -32,6 +35,7 @@ __global__ __launch_bounds__(512) void k16(float* out, int iters) {
 int main() {
   float* out; hipMalloc(&out, 256 * 8 * 1024 * 4);
   hipEvent_t e0, e1; hipEventCreate(&e0); hipEventCreate(&e1);
+  double best = 0.0;
   auto run = [&](const char* name, auto kern, int threads, int nacc, double flop_per_mfma, int grid) {
     int iters = 20000;
     hipLaunchKernelGGL(kern, grid, threads, 0, 0, out, 100); hipDeviceSynchronize();
@@ -39,6 +43,7 @@ int main() {
     float ms; hipEventElapsedTime(&ms, e0, e1);
     double fl = (double)grid * (threads / 64) * iters * nacc * flop_per_mfma;
     printf("%-34s %8.3f ms  %8.1f TFLOP/s\n", name, ms, fl / ms / 1e9);
+    if (fl / ms / 1e9 > best) best = fl / ms / 1e9;
   };
   run("32x32x16 4acc 8w/CU x256", k32<4>, 512, 4, 32768.0, 256);
   run("32x32x16 2acc 8w/CU x256", k32<2>, 512, 2, 32768.0, 256);
@@ -47,5 +52,6 @@ int main() {
   run("16x16x32 4acc 8w/CU x256", k16<4>, 512, 4, 16384.0, 256);
   run("16x16x32 8acc 8w/CU x256", k16<8>, 512, 8, 16384.0, 256);
   run("32x32x16 4acc 8w/CU x256 (again)", k32<4>, 512, 4, 32768.0, 256);
+  printf("RESULT mfma_bf16_tflops=%.1f\n", best);
   return 0;
 }

@@ -61,3 +61,25 @@ def test_zero_keys_closed_form_pins_the_mask_through_the_kernel():
         js = [j for j in range(i + 1) if (bi - j // B) < W or j // B < S or bin(bi - j // B).count("1") <= 1]
         assert abs(lse[0, 0, i] - math.log(len(js))) < 1e-5
         assert np.abs(o[0, 0, i] - vv[js].mean(axis=0)).max() < 1e-5
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_a_query_block_with_an_empty_list_gives_zero_output_and_minus_infinity(dtype):
+    # A caller's own list may leave a query block without any key block (Equation 1 over an empty attended
+    # set): both kernels then write o = 0 and lse = -inf for its rows, and the other rows are unaffected.
+    n, B = 512, 64
+    pat = pa.Pattern(B, 2, 1)
+    q, k, v = synth.qkv(1, 2, 2, n, 64, dtype, seed=17)
+    cnt, idx, _ = pa.mask_build(pat, n)
+    torch.cuda.synchronize()
+    ref_o, ref_l = gpu_prefill(pat, q, k, v, lists=(cnt, idx))
+    cnt2, idx2 = cnt.clone(), idx.clone()
+    cnt2[3] = 0
+    idx2[3] = -1
+    o, lse = gpu_prefill(pat, q, k, v, lists=(cnt2, idx2))
+    rows = slice(3 * B, 4 * B)
+    assert (o[:, :, rows] == 0).all()
+    assert np.isneginf(lse[:, :, rows]).all()
+    keep = np.ones(n, dtype=bool)
+    keep[rows] = False
+    assert np.array_equal(o[:, :, keep], ref_o[:, :, keep]) and np.array_equal(lse[:, :, keep], ref_l[:, :, keep])
