@@ -202,11 +202,13 @@ size_t powattn_decode_workspace_bytes(const powattn_pattern* pattern, int32_t ba
  *   lse            device float [batch, n_q_heads] or NULL
  *   dtype          POWATTN_BF16 only; head_dim 64 or 128; block a multiple of 64, at most 1024
  *   workspace      device, at least powattn_decode_workspace_bytes(...) bytes,
- *                  256-byte aligned; contents on entry are ignored.  Two calls
- *                  that may run at the same time must not share a workspace,
- *                  and at most 64 calls may be in flight at once per device
- *                  (the workgroups of a call count themselves in through one
- *                  of 64 sets of counters in the library's device memory).
+ *                  256-byte aligned; needs no initialisation.  It holds the
+ *                  partial results of the workgroups that share a (sequence,
+ *                  KV head), each value tagged with a generation number that is
+ *                  also kept there and advanced by every call, so that a call
+ *                  tells its own partials from whatever the memory held before.
+ *                  Two calls that may run at the same time must not share a
+ *                  workspace; there is no other limit on calls in flight.
  * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR.
  */
 int powattn_decode(const powattn_pattern* pattern,

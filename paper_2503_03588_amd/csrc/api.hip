@@ -219,10 +219,40 @@ extern "C" size_t powattn_decode_workspace_bytes(const powattn_pattern* pattern,
   if (n_q_heads % n_kv_heads != 0) return 0;
   int32_t ns = pa_decode_splits(pattern, batch, n_kv_heads, cache_capacity);
   if (ns < 1) return 0;
-  // per (batch, q head, split): head_dim unnormalised outputs + running max + running sum.
-  // With a single split the kernel writes the result directly and the buffer is not touched.
-  size_t partials = (size_t)batch * n_q_heads * ns * (size_t)(head_dim + 2) * sizeof(float);
-  return (partials + 255) & ~(size_t)255;
+  // a generation number per (batch, KV head); per (batch, q head, split): head_dim unnormalised outputs +
+  // running max + running sum, as 8-byte packets.  With a single split the kernel writes the result directly.
+  return pa_decode_workspace_layout(batch, n_q_heads, n_kv_heads, head_dim, ns, nullptr);
+}
+
+// The three decode entry points share everything but where the cache and the workspace come from.
+static int decode_common(const powattn_pattern* pattern, const void* q, const void* k, const void* v,
+                         const int32_t* d_kv_len, int64_t capacity, void* o, float* lse,
+                         int32_t batch, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                         int32_t dtype, float softmax_scale, void* workspace, size_t workspace_bytes,
+                         const int32_t* block_table, int32_t table_stride, int64_t n_pages, void* hip_stream) {
+  if (!(softmax_scale == softmax_scale)) return POWATTN_INVALID_ARG;
+  if (dtype != POWATTN_BF16) return POWATTN_UNSUPPORTED;
+  if (!supported_head_dim(head_dim)) return POWATTN_UNSUPPORTED;
+  if (pattern->block % 64 != 0 || pattern->block > 1024) return POWATTN_UNSUPPORTED;
+  if (pattern->flags & POWATTN_DENSE) return POWATTN_UNSUPPORTED;
+  if (n_q_heads / n_kv_heads > 16) return POWATTN_UNSUPPORTED;
+  if (powattn_num_blocks(pattern, capacity) < 0) return POWATTN_INVALID_ARG;
+  size_t need = powattn_decode_workspace_bytes(pattern, batch, n_q_heads, n_kv_heads, head_dim, capacity);
+  if (need == 0) return POWATTN_INVALID_ARG;
+  if (!workspace || workspace_bytes < need) return POWATTN_WORKSPACE_TOO_SMALL;
+  if (((uintptr_t)workspace & 255u) != 0) return POWATTN_INVALID_ARG;
+
+  pa_decode_args a;
+  a.pat = *pattern;
+  a.q = q; a.k = k; a.v = v; a.kv_len = d_kv_len; a.capacity = capacity;
+  a.o = o; a.lse = lse;
+  a.batch = batch; a.hq = n_q_heads; a.hkv = n_kv_heads; a.head_dim = head_dim;
+  a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)head_dim);
+  a.workspace = workspace;
+  a.n_split = pa_decode_splits(pattern, batch, n_kv_heads, capacity);
+  a.stream = (hipStream_t)hip_stream;
+  a.block_table = block_table; a.table_stride = table_stride; a.n_pages = n_pages;
+  return pa_launch_decode_bf16(a);
 }
 
 extern "C" int powattn_decode(const powattn_pattern* pattern,
@@ -237,29 +267,8 @@ extern "C" int powattn_decode(const powattn_pattern* pattern,
   if (!q || !k_cache || !v_cache || !d_kv_len || !o) return POWATTN_INVALID_ARG;
   if (batch < 1 || n_q_heads < 1 || n_kv_heads < 1 || head_dim < 1 || cache_capacity < 1) return POWATTN_INVALID_ARG;
   if (n_q_heads % n_kv_heads != 0) return POWATTN_INVALID_ARG;
-  if (!(softmax_scale == softmax_scale)) return POWATTN_INVALID_ARG;
-  if (dtype != POWATTN_BF16) return POWATTN_UNSUPPORTED;
-  if (!supported_head_dim(head_dim)) return POWATTN_UNSUPPORTED;
-  if (pattern->block % 64 != 0 || pattern->block > 1024) return POWATTN_UNSUPPORTED;
-  if (pattern->flags & POWATTN_DENSE) return POWATTN_UNSUPPORTED;
-  if (n_q_heads / n_kv_heads > 16) return POWATTN_UNSUPPORTED;
-  if (powattn_num_blocks(pattern, cache_capacity) < 0) return POWATTN_INVALID_ARG;
-  size_t need = powattn_decode_workspace_bytes(pattern, batch, n_q_heads, n_kv_heads, head_dim, cache_capacity);
-  if (need == 0) return POWATTN_INVALID_ARG;
-  if (!workspace || workspace_bytes < need) return POWATTN_WORKSPACE_TOO_SMALL;
-  if (((uintptr_t)workspace & 255u) != 0) return POWATTN_INVALID_ARG;
-
-  pa_decode_args a;
-  a.pat = *pattern;
-  a.q = q; a.k = k_cache; a.v = v_cache; a.kv_len = d_kv_len; a.capacity = cache_capacity;
-  a.o = o; a.lse = lse;
-  a.batch = batch; a.hq = n_q_heads; a.hkv = n_kv_heads; a.head_dim = head_dim;
-  a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)head_dim);
-  a.workspace = workspace;
-  a.n_split = pa_decode_splits(pattern, batch, n_kv_heads, cache_capacity);
-  a.stream = (hipStream_t)hip_stream;
-  a.block_table = nullptr; a.table_stride = 0; a.n_pages = 0;
-  return pa_launch_decode_bf16(a);
+  return decode_common(pattern, q, k_cache, v_cache, d_kv_len, cache_capacity, o, lse, batch, n_q_heads, n_kv_heads,
+                       head_dim, dtype, softmax_scale, workspace, workspace_bytes, nullptr, 0, 0, hip_stream);
 }
 
 extern "C" int powattn_decode_paged(const powattn_pattern* pattern,
@@ -275,30 +284,10 @@ extern "C" int powattn_decode_paged(const powattn_pattern* pattern,
   if (!q || !k_pages || !v_pages || !d_block_table || !d_kv_len || !o) return POWATTN_INVALID_ARG;
   if (batch < 1 || n_q_heads < 1 || n_kv_heads < 1 || head_dim < 1 || n_pages < 1 || table_stride < 1) return POWATTN_INVALID_ARG;
   if (n_q_heads % n_kv_heads != 0) return POWATTN_INVALID_ARG;
-  if (!(softmax_scale == softmax_scale)) return POWATTN_INVALID_ARG;
-  if (dtype != POWATTN_BF16) return POWATTN_UNSUPPORTED;
-  if (!supported_head_dim(head_dim)) return POWATTN_UNSUPPORTED;
-  if (pattern->block % 64 != 0 || pattern->block > 1024) return POWATTN_UNSUPPORTED;
-  if (pattern->flags & POWATTN_DENSE) return POWATTN_UNSUPPORTED;
-  if (n_q_heads / n_kv_heads > 16) return POWATTN_UNSUPPORTED;
   const int64_t capacity = (int64_t)table_stride * pattern->block;      // tokens a sequence's table can hold
-  if (powattn_num_blocks(pattern, capacity) < 0) return POWATTN_INVALID_ARG;
-  size_t need = powattn_decode_workspace_bytes(pattern, batch, n_q_heads, n_kv_heads, head_dim, capacity);
-  if (need == 0) return POWATTN_INVALID_ARG;
-  if (!workspace || workspace_bytes < need) return POWATTN_WORKSPACE_TOO_SMALL;
-  if (((uintptr_t)workspace & 255u) != 0) return POWATTN_INVALID_ARG;
-
-  pa_decode_args a;
-  a.pat = *pattern;
-  a.q = q; a.k = k_pages; a.v = v_pages; a.kv_len = d_kv_len; a.capacity = capacity;
-  a.o = o; a.lse = lse;
-  a.batch = batch; a.hq = n_q_heads; a.hkv = n_kv_heads; a.head_dim = head_dim;
-  a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)head_dim);
-  a.workspace = workspace;
-  a.n_split = pa_decode_splits(pattern, batch, n_kv_heads, capacity);
-  a.stream = (hipStream_t)hip_stream;
-  a.block_table = d_block_table; a.table_stride = table_stride; a.n_pages = n_pages;
-  return pa_launch_decode_bf16(a);
+  return decode_common(pattern, q, k_pages, v_pages, d_kv_len, capacity, o, lse, batch, n_q_heads, n_kv_heads,
+                       head_dim, dtype, softmax_scale, workspace, workspace_bytes,
+                       d_block_table, table_stride, n_pages, hip_stream);
 }
 
 extern "C" size_t powattn_backward_workspace_bytes(const powattn_pattern* pattern, int32_t batch, int32_t n_q_heads,

@@ -57,6 +57,9 @@ struct pa_decode_args {
   int64_t n_pages;
 };
 int pa_launch_decode_bf16(const pa_decode_args& a);
+// total workspace bytes of a decode call with n_split workgroups per (sequence, KV head); *header_bytes (may be
+// null) receives the size of the generation numbers at its start
+size_t pa_decode_workspace_layout(int32_t batch, int32_t hq, int32_t hkv, int32_t head_dim, int32_t n_split, size_t* header_bytes);
 
 struct pa_backward_args {
   powattn_pattern pat;

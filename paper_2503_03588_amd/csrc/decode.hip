@@ -21,17 +21,21 @@
 //    accumulator layout of S^T is the B-operand layout of the second product.
 //  * Each wavefront keeps a running (max, sum, O) over its chunks; the eight
 //    partials meet in LDS.  With one workgroup per (sequence, KV head) that is
-//    the result; with several, the workgroups leave unnormalised partials in
-//    the workspace and the one that arrives last (an arrival counter per
-//    (sequence, KV head)) merges them: a second launch would cost more than
-//    the whole merge.  Partials, counter and the merging loads act at device
-//    scope by themselves; no fence is used, because a device-scope fence writes
-//    back and invalidates a whole L2 on this chip.
+//    the result; with several, every workgroup leaves its unnormalised partial
+//    in the workspace as tagged 8-byte packets, waits until memory has taken
+//    them, and then reads the packets of the other workgroups: the one whose
+//    packets landed last finds all of them in place and writes the output (a
+//    second launch would cost more than the whole merge).  There are no
+//    counters and nothing in the workspace has to be initialised: a packet
+//    is valid when its tag matches the generation number that the (sequence,
+//    KV head) keeps in the workspace and that the finishing workgroup advances.
+//    Packet stores and loads act at device scope by themselves; no fence is
+//    used, because a device-scope fence writes back and invalidates a whole L2
+//    on this chip.
 //  * With several work items per compute unit (large batches) persistent
 //    workgroups take over (pa_decode_stream_kernel): the loads of the next item
 //    are in flight while the current one is merged.
 #include <math.h>
-#include <atomic>
 #include "common.h"
 
 namespace {
@@ -47,24 +51,52 @@ constexpr int MAXG = 16;       // query heads per KV head (columns of the MFMA t
 struct dec_params {
   const __bf16* q; const __bf16* k; const __bf16* v; const int32_t* kv_len;
   __bf16* o; float* lse;
-  float* partials;      // [batch, hq, splits, D + 2] when splits > 1
+  float* partials;      // [batch, hq, splits, D + 2] floats when splits > 1 and a merge kernel follows
+  uint64_t* packets;    // the same shape as (value, tag) packets when the workgroups merge among themselves
+  uint32_t* gen;        // [batch, hkv] generation numbers of the packets (any initial value)
   int64_t capacity;
   int32_t B, W, S; uint32_t flags;
   int32_t hq, hkv, G, splits, subs;
   uint32_t subs_magic;  // ceil(2^32 / subs) for subs > 1: slot / subs = umulhi(slot, subs_magic) for every slot of a row
-  int32_t fused;        // 1: the last workgroup of a (sequence, KV head) merges the partials itself
-  int32_t region;       // which set of arrival counters this call uses
+  int32_t fused;        // 1: the workgroups of a (sequence, KV head) merge their partials among themselves
   float c2;
   const int32_t* block_table;   // paged cache: page of block j of sequence b at [b * table_stride + j]; else null
   int32_t table_stride;
   int64_t n_pages;
 };
 
-// Arrival counters of the fused merge: one per (sequence, KV head) and call in flight.  They live in the
-// library's own device memory (zero when the module is loaded, set back to zero by the last arriver), so the
-// caller's workspace needs no initialisation; calls take the sets round-robin.
-constexpr int CTR_SETS = 64, CTR_PER_SET = 4096;
-__device__ unsigned int g_arrivals[CTR_SETS][CTR_PER_SET];
+// ---- merging the workgroups of a (sequence, KV head) without a second kernel ----
+// Every value of a partial result travels as one 8-byte packet (value, tag), written and read with single 8-byte
+// device-scope accesses, so a reader sees a value together with its tag or not at all.  The tag is derived from the
+// generation number g that the (sequence, KV head) keeps in the workspace, read at the start of the kernel, and from
+// the split.  Protocol of a workgroup: store its packets; wait until memory has acknowledged every one of them
+// (s_waitcnt, then the workgroup's barrier); load the packets of the other splits; if every tag is the expected one,
+// combine all partials in split order, write the output and store g + 1 as the new generation.
+//  * Some workgroup finishes: order the workgroups by the time at which the last of their stores was acknowledged;
+//    the latest one loads after that, when every other workgroup's packets are in memory.
+//  * Several may finish: they combine the same values in the same order and write the same bits.
+//  * Nothing stale is taken for valid: what the workspace holds from the call before carries generation g - 1 (the
+//    finisher advanced it only after every workgroup of the pair had stored, hence had read g), and the very first
+//    call on a workspace meets whatever the memory held: a word there passes for a tag only if it equals
+//    ~g ^ ((split + 1) << 24) for the word g found in the same memory (never for a memory filled with one byte
+//    value, zeros included).
+//  * No workgroup waits for another one: whoever finds a packet missing simply leaves.
+// Calls that may run at the same time must not share a workspace (they would share generation numbers).
+constexpr int MAX_FUSED_SPLITS = 16;
+__device__ __forceinline__ uint32_t dec_tag(uint32_t gen, int split) { return ~gen ^ ((uint32_t)(split + 1) << 24); }
+__device__ __forceinline__ void dec_put(uint64_t* slot, float x, uint32_t tag) {
+  __hip_atomic_store(slot, ((uint64_t)tag << 32) | __builtin_bit_cast(uint32_t, x), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint64_t dec_get(const uint64_t* slot) {
+  return __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// LDS layout of the wavefronts' partial outputs: the 32 values a lane holds (d = 32*q4 + x) form a row of 36 floats,
+// so that the 16 lanes of a store (4 heads x 4 groups) start 36 floats apart and cover all banks between them.
+constexpr int OROW = 36;
+template <int D>
+__device__ __forceinline__ int dec_o_at(int wave, int G, int g, int d) { return (((wave * G + g) * (D / 32) + (d >> 5)) * OROW) + (d & 31); }
+template <int D>
+constexpr size_t dec_o_bytes(int G) { return (size_t)NW * G * (D / 32) * OROW * sizeof(float); }
 
 // The query's row of the pattern in closed form: [0, sink_end) ++ {i - 2^k inside [pow_lo, win_start), k
 // descending} ++ [win_start, i].  Uniform over a workgroup, so all of it runs on the scalar unit.
@@ -228,16 +260,44 @@ __device__ __forceinline__ void dec_load_q(bf16x8 (&qf)[D / 32], const dec_param
     qf[c] = g < p.G ? *reinterpret_cast<const bf16x8*>(qp + 32 * c + 8 * q4) : z;
 }
 
+// The wavefront's partial output into LDS: lane (g, q4) holds O[j][r] = o[g][d = 32*q4 + 8r + j], eight
+// consecutive d per r, written as two 16-byte stores into the lane's padded row.
+template <int D>
+__device__ __forceinline__ void dec_stash(float* s_o, int wave, int G, int g, int q4, const f32x4 (&O)[8]) {
+  if (32 * q4 >= D) return;
+  f32x4* row = reinterpret_cast<f32x4*>(s_o + dec_o_at<D>(wave, G, g, 32 * q4));
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    row[2 * r] = f32x4{O[0][r], O[1][r], O[2][r], O[3][r]};
+    row[2 * r + 1] = f32x4{O[4][r], O[5][r], O[6][r], O[7][r]};
+  }
+}
+
 template <int D>
 __global__ __launch_bounds__(64 * NW) void pa_decode_kernel(dec_params p) {
   __shared__ float s_m[NW][MAXG], s_l[NW][MAXG];
-  extern __shared__ float s_o_dyn[];            // [NW][G][D] partial outputs of the wavefronts
+  extern __shared__ __attribute__((aligned(16))) float s_o_dyn[];   // [NW][G][D/32][OROW] partial outputs of the wavefronts
 
   const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  // the wavefront's number as a scalar and the lane from the hardware's lane count: the thread index itself need
+  // not stay in a vector register through the chunk loop, where every register counts
+  const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+  const int lane = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
   const int g = lane & 15, q4 = lane >> 4;    // column (query head) and k-group of this lane
 
-  const dec_row row = dec_row_of(p, p.kv_len[b]);
+  // The sequence length and the generation of this (sequence, KV head)'s packets (needed only at the end) are
+  // both uniform: two scalar loads, one wait.  Written as assembly so that the generation number lives in a
+  // scalar register from the start (a vector register held across the chunk loop costs a spill to scratch
+  // memory, and a kernel that uses scratch memory starts later).  Both words were written before this kernel
+  // started, so the scalar cache, which is empty at the start of a kernel, returns what memory holds.
+  uint32_t gen;
+  int len_b;
+  asm volatile("s_load_dword %0, %2, 0x0\n\ts_load_dword %1, %3, 0x0\n\ts_waitcnt lgkmcnt(0)"
+               : "=&s"(gen), "=&s"(len_b)
+               : "s"(p.gen + (int64_t)b * p.hkv + kvh), "s"(p.kv_len + b)
+               : "memory");
+
+  const dec_row row = dec_row_of(p, len_b);
   bf16x8 qf[D / 32];
   dec_load_q<D>(qf, p, b, kvh, g, q4);
 
@@ -260,22 +320,24 @@ __global__ __launch_bounds__(64 * NW) void pa_decode_kernel(dec_params p) {
     dec_consume<D>(c, qf, pl.n_tok, p.c2, q4, m_run, l_run, O);
   }
 
-  // ---- merge the wavefronts: lane (g, q4) holds O[j][r] = o[g][d = 8(4*q4 + r) + j] ----
+  // ---- merge the wavefronts through LDS ----
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
   if (g < p.G) {
     if (q4 == 0) { s_m[wave][g] = m_run; s_l[wave][g] = l_run; }
-#pragma unroll
-    for (int j = 0; j < 8; ++j)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int d = 8 * (4 * q4 + r) + j;
-        if (d < D) s_o_dyn[((wave * p.G) + g) * D + d] = O[j][r];
-      }
+    dec_stash<D>(s_o_dyn, wave, p.G, g, q4, O);
   }
   __syncthreads();
 
-  for (int e = tid; e < p.G * D; e += 64 * NW) {
+  // thread e owns output (head gg, component d); with up to 16 heads per KV head a thread owns several
+  const int tid = wave * 64 + (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+  constexpr int EPT = MAXG * D / (64 * NW);            // at most this many outputs per thread
+  float accs[EPT], Ms[EPT], Ls[EPT];
+#pragma unroll
+  for (int x = 0; x < EPT; ++x) {
+    const int e = tid + x * 64 * NW;
+    accs[x] = 0.f; Ms[x] = -INFINITY; Ls[x] = 0.f;
+    if (e >= p.G * D) continue;
     const int gg = e / D, d = e % D;
     float M = -INFINITY;
 #pragma unroll
@@ -285,58 +347,86 @@ __global__ __launch_bounds__(64 * NW) void pa_decode_kernel(dec_params p) {
     for (int w = 0; w < NW; ++w) {
       const float wt = s_l[w][gg] > 0.f ? __builtin_amdgcn_exp2f(s_m[w][gg] - M) : 0.f;
       L = fmaf(wt, s_l[w][gg], L);
-      acc = fmaf(wt, s_o_dyn[((w * p.G) + gg) * D + d], acc);
+      acc = fmaf(wt, s_o_dyn[dec_o_at<D>(w, p.G, gg, d)], acc);
     }
+    accs[x] = acc; Ms[x] = M; Ls[x] = L;
     const int h = kvh * p.G + gg;
     if (p.splits == 1) {
       p.o[((int64_t)b * p.hq + h) * D + d] = (__bf16)(acc / L);      // L > 0: chunk 0 of the row is never empty
       if (p.lse && d == 0) p.lse[(int64_t)b * p.hq + h] = (M + log2f(L)) * 0.69314718055994530942f;
-    } else {
-      // Partials go to memory with device scope (written through this XCD's L2): the workgroup that merges
-      // them may sit on another XCD, whose L2 would not see lines that only live in ours.
+    } else if (!p.fused) {
+      // a merge kernel follows: plain stores
       float* part = p.partials + (((int64_t)b * p.hq + h) * p.splits + split) * (D + 2);
-      __hip_atomic_store(part + d, acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (d == 0) {                                                  // an idle split leaves M = -inf, L = 0
-        __hip_atomic_store(part + D, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(part + D + 1, L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
+      part[d] = acc;
+      if (d == 0) { part[D] = M; part[D + 1] = L; }                  // an idle split leaves M = -inf, L = 0
+    } else {
+      uint64_t* pk = p.packets + (((int64_t)b * p.hq + h) * p.splits + split) * (D + 2);
+      const uint32_t tag = dec_tag(gen, split);
+      dec_put(pk + d, acc, tag);
+      if (d == 0) { dec_put(pk + D, M, tag); dec_put(pk + D + 1, L, tag); }
     }
   }
   if (p.splits == 1 || !p.fused) return;
 
-  // ---- fused merge: the workgroup that arrives last at its (sequence, KV head) combines all partials ----
-  // Every store above has been acknowledged by memory before its thread passes the barrier; then one
-  // thread counts the workgroup in.  No fence is involved: the stores, the counter and the loads below all act
-  // at device scope themselves, and a fence would write back and invalidate this XCD's whole L2.
-  __shared__ unsigned int s_rank;
-  __builtin_amdgcn_s_waitcnt(0);                                     // vmcnt(0), lgkmcnt(0)
-  __syncthreads();
-  unsigned int* ctr = &g_arrivals[p.region][b * p.hkv + kvh];
-  if (tid == 0) s_rank = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  __syncthreads();
-  if (s_rank != (unsigned)p.splits - 1) return;
-  if (tid == 0) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  for (int e = tid; e < p.G * D; e += 64 * NW) {
+  // ---- the workgroups of this (sequence, KV head) merge among themselves (protocol above) ----
+  __builtin_amdgcn_s_waitcnt(0);                       // vmcnt(0): memory has acknowledged this thread's packets
+  __syncthreads();                                     // ... and every other thread's of this workgroup
+  bool valid = true;
+  float o_out[EPT], lse_out[EPT];
+#pragma unroll
+  for (int x = 0; x < EPT; ++x) {
+    const int e = tid + x * 64 * NW;
+    o_out[x] = 0.f; lse_out[x] = 0.f;
+    if (e >= p.G * D) continue;
     const int gg = e / D, d = e % D;
     const int h = kvh * p.G + gg;
-    const float* part = p.partials + ((int64_t)b * p.hq + h) * p.splits * (D + 2);
+    const uint64_t* pk = p.packets + ((int64_t)b * p.hq + h) * p.splits * (D + 2);
     float M = -INFINITY, L = 0.f, acc = 0.f;
-    for (int s0 = 0; s0 < p.splits; ++s0) {
-      const float* ps = part + (int64_t)s0 * (D + 2);
-      const float ms = __hip_atomic_load(ps + D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      const float ls = __hip_atomic_load(ps + D + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      const float os = __hip_atomic_load(ps + d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (ls > 0.f) {                                                // idle splits hold no outputs
-        const float Mn = fmaxf(M, ms);
-        const float r0 = L > 0.f ? __builtin_amdgcn_exp2f(M - Mn) : 0.f, r1 = __builtin_amdgcn_exp2f(ms - Mn);
-        L = L * r0 + ls * r1;
-        acc = acc * r0 + os * r1;
-        M = Mn;
+    for (int s0 = 0; s0 < p.splits; s0 += 8) {
+      uint64_t pm[8], pl[8], po[8];
+#pragma unroll
+      for (int y = 0; y < 8; ++y) {                    // all loads of (up to) eight splits before any is looked at
+        pm[y] = pl[y] = po[y] = 0;
+        if (s0 + y < p.splits && s0 + y != split) {    // uniform over the workgroup; its own partial is in registers
+          const uint64_t* ps = pk + (int64_t)(s0 + y) * (D + 2);
+          pm[y] = dec_get(ps + D); pl[y] = dec_get(ps + D + 1); po[y] = dec_get(ps + d);
+        }
+      }
+#pragma unroll
+      for (int y = 0; y < 8; ++y) {
+        const int s1 = s0 + y;
+        if (s1 >= p.splits) break;
+        float ms, ls, os;
+        if (s1 == split) { ms = Ms[x]; ls = Ls[x]; os = accs[x]; }   // this workgroup's own partial: the same bits
+        else {
+          const uint32_t want = dec_tag(gen, s1);
+          valid = valid && (uint32_t)(pm[y] >> 32) == want && (uint32_t)(pl[y] >> 32) == want && (uint32_t)(po[y] >> 32) == want;
+          ms = __builtin_bit_cast(float, (uint32_t)pm[y]); ls = __builtin_bit_cast(float, (uint32_t)pl[y]);
+          os = __builtin_bit_cast(float, (uint32_t)po[y]);
+        }
+        if (ls > 0.f) {                                              // idle splits hold no outputs
+          const float Mn = fmaxf(M, ms);
+          const float r0 = L > 0.f ? __builtin_amdgcn_exp2f(M - Mn) : 0.f, r1 = __builtin_amdgcn_exp2f(ms - Mn);
+          L = L * r0 + ls * r1;
+          acc = acc * r0 + os * r1;
+          M = Mn;
+        }
       }
     }
-    p.o[((int64_t)b * p.hq + h) * D + d] = (__bf16)(acc / L);
-    if (p.lse && d == 0) p.lse[(int64_t)b * p.hq + h] = (M + log2f(L)) * 0.69314718055994530942f;
+    o_out[x] = acc / L;
+    lse_out[x] = (M + log2f(L)) * 0.69314718055994530942f;
   }
+  if (!__syncthreads_and(valid ? 1 : 0)) return;       // some packet has not landed: its workgroup will finish
+#pragma unroll
+  for (int x = 0; x < EPT; ++x) {
+    const int e = tid + x * 64 * NW;
+    if (e >= p.G * D) continue;
+    const int gg = e / D, d = e % D;
+    const int h = kvh * p.G + gg;
+    p.o[((int64_t)b * p.hq + h) * D + d] = (__bf16)o_out[x];
+    if (p.lse && d == 0) p.lse[(int64_t)b * p.hq + h] = lse_out[x];
+  }
+  if (tid == 0) __hip_atomic_store(p.gen + (int64_t)b * p.hkv + kvh, gen + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Large batches: persistent workgroups.  With many more (sequence, KV head, split) items than compute units the
@@ -350,9 +440,11 @@ __global__ __launch_bounds__(64 * NW) void pa_decode_kernel(dec_params p) {
 template <int D>
 __global__ __launch_bounds__(64 * NW) void pa_decode_stream_kernel(dec_params p, int n_items) {
   __shared__ float s_m[2][NW][MAXG], s_l[2][NW][MAXG];
-  extern __shared__ float s_o_dyn[];            // [2][NW][G][D] partial outputs of the wavefronts, two items
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  extern __shared__ __attribute__((aligned(16))) float s_o_dyn[];   // [2][NW][G][D/32][OROW] partial outputs of the wavefronts, two items
+  // (wavefront number as a scalar, lane from the hardware's lane count: see pa_decode_kernel)
+  const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+  const int lane = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+  const int tid = wave * 64 + lane;
   const int g = lane & 15, q4 = lane >> 4;
   const int stride = (int)gridDim.x;
   const int per_b = p.hkv * p.splits;
@@ -401,7 +493,7 @@ __global__ __launch_bounds__(64 * NW) void pa_decode_stream_kernel(dec_params p,
 
   for (int n = 0; w < n_items; w += stride, ++n) {
     const int buf = n & 1;
-    float* s_o = s_o_dyn + (size_t)buf * NW * p.G * D;
+    float* s_o = s_o_dyn + (size_t)buf * (dec_o_bytes<D>(p.G) / sizeof(float));
     // ---- this wavefront's chunk of the current item ----
     float m_run = -INFINITY, l_run = 0.f;
     f32x4 O[8];
@@ -412,13 +504,7 @@ __global__ __launch_bounds__(64 * NW) void pa_decode_stream_kernel(dec_params p,
     l_run += __shfl_xor(l_run, 32);
     if (g < p.G) {
       if (q4 == 0) { s_m[buf][wave][g] = m_run; s_l[buf][wave][g] = l_run; }
-#pragma unroll
-      for (int j = 0; j < 8; ++j)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int d = 8 * (4 * q4 + r) + j;
-          if (d < D) s_o[((wave * p.G) + g) * D + d] = O[j][r];
-        }
+      dec_stash<D>(s_o, wave, p.G, g, q4, O);
     }
     // ---- the next item's bytes are requested before this one is merged ----
     const item_t done = cur.it;
@@ -439,7 +525,7 @@ __global__ __launch_bounds__(64 * NW) void pa_decode_stream_kernel(dec_params p,
       for (int wv = 0; wv < NW; ++wv) {
         const float wt = s_l[buf][wv][gg] > 0.f ? __builtin_amdgcn_exp2f(s_m[buf][wv][gg] - M) : 0.f;
         L = fmaf(wt, s_l[buf][wv][gg], L);
-        acc = fmaf(wt, s_o[((wv * p.G) + gg) * D + d], acc);
+        acc = fmaf(wt, s_o[dec_o_at<D>(wv, p.G, gg, d)], acc);
       }
       const int h = done.kvh * p.G + gg;
       if (p.splits == 1) {
@@ -522,48 +608,52 @@ int32_t pa_decode_splits(const powattn_pattern* pat, int32_t batch, int32_t hkv,
   return (int32_t)s;
 }
 
+// Workspace of a decode call: the generation numbers of the (sequence, KV head) pairs (one 32-bit word each,
+// padded to 256 bytes), then room for the partial results as 8-byte packets (the float form of the two-kernel
+// merge uses the first half of it).
+size_t pa_decode_workspace_layout(int32_t batch, int32_t hq, int32_t hkv, int32_t head_dim, int32_t n_split, size_t* header_bytes) {
+  const size_t hdr = ((size_t)batch * hkv * sizeof(uint32_t) + 255) & ~(size_t)255;
+  if (header_bytes) *header_bytes = hdr;
+  const size_t partials = (size_t)batch * hq * n_split * (size_t)(head_dim + 2) * sizeof(uint64_t);
+  return hdr + ((partials + 255) & ~(size_t)255);
+}
+
 int pa_launch_decode_bf16(const pa_decode_args& a) {
   if (a.n_split < 1) return POWATTN_UNSUPPORTED;
   if (a.hkv > 65535 || a.batch > 65535 || a.hq > 65535 * 16) return POWATTN_UNSUPPORTED;
   dec_params p;
   p.q = (const __bf16*)a.q; p.k = (const __bf16*)a.k; p.v = (const __bf16*)a.v; p.kv_len = a.kv_len;
   p.o = (__bf16*)a.o; p.lse = a.lse;
-  p.partials = (float*)a.workspace;
+  size_t hdr = 0;
+  pa_decode_workspace_layout(a.batch, a.hq, a.hkv, a.head_dim, a.n_split, &hdr);
+  p.gen = (uint32_t*)a.workspace;
+  p.packets = (uint64_t*)((char*)a.workspace + hdr);
+  p.partials = (float*)((char*)a.workspace + hdr);
   p.capacity = a.capacity;
   p.B = a.pat.block; p.W = a.pat.window; p.S = a.pat.sink; p.flags = a.pat.flags;
   p.hq = a.hq; p.hkv = a.hkv; p.G = a.hq / a.hkv; p.splits = a.n_split; p.subs = a.pat.block / CH;
   p.subs_magic = p.subs > 1 ? (uint32_t)(((1ull << 32) + p.subs - 1) / p.subs) : 0u;
   p.c2 = a.scale * 1.44269504088896340736f;
   p.block_table = a.block_table; p.table_stride = a.table_stride; p.n_pages = a.n_pages;
-  static std::atomic<unsigned> next_region{0};
-  p.fused = (a.n_split > 1 && a.n_split <= 64 && (int64_t)a.batch * a.hkv <= CTR_PER_SET) ? 1 : 0;
-  p.region = p.fused ? (int32_t)(next_region.fetch_add(1) % CTR_SETS) : 0;
+  // few enough splits that every workgroup can afford to read all the others' partials: they merge among
+  // themselves; otherwise the merge kernel follows
+  p.fused = (a.n_split > 1 && a.n_split <= MAX_FUSED_SPLITS) ? 1 : 0;
+  int n_cu = 1;
+  pa_current_device(nullptr, &n_cu);
   // Many more items than compute units, every row a single pass: persistent workgroups that keep bytes in flight
   // across items, then the merge kernel.
   {
-    static int n_cu[64] = {0};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) dev = 0;
-    if (n_cu[dev] == 0) {
-      int v = 0;
-      if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1) v = 1;
-      n_cu[dev] = v;
-    }
     const int64_t items = (int64_t)a.batch * a.hkv * a.n_split;
     const int64_t max_slots = (int64_t)powattn_max_k(&a.pat, a.capacity) * p.subs;
-    if (items >= 4 * (int64_t)n_cu[dev] && items <= 0x7fffffff / 4 && max_slots <= (int64_t)a.n_split * NW) {
+    if (items >= 4 * (int64_t)n_cu && items <= 0x7fffffff / 4 && max_slots <= (int64_t)a.n_split * NW) {
       p.fused = 0;
-      const size_t lds2 = 2 * (size_t)NW * p.G * a.head_dim * sizeof(float);   // at most 128 KB
-      static bool attr_done[2] = {false, false};
+      const size_t lds2 = 2 * (a.head_dim == 128 ? dec_o_bytes<128>(p.G) : dec_o_bytes<64>(p.G));   // at most 144 KB
+      static std::atomic<unsigned long long> attr_done[2];
       const int which = a.head_dim == 128 ? 0 : 1;
       const void* fn = which == 0 ? reinterpret_cast<const void*>(&pa_decode_stream_kernel<128>)
                                   : reinterpret_cast<const void*>(&pa_decode_stream_kernel<64>);
-      if (!attr_done[which]) {
-        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(2 * (size_t)NW * MAXG * 128 * sizeof(float)));
-        if (e != hipSuccess) return pa_note_hip(e);
-        attr_done[which] = true;
-      }
-      const dim3 pgrid((uint32_t)n_cu[dev]);
+      if (int st = pa_allow_dynamic_lds(fn, 2 * (which == 0 ? dec_o_bytes<128>(MAXG) : dec_o_bytes<64>(MAXG)), attr_done[which])) return st;
+      const dim3 pgrid((uint32_t)n_cu);
       if (a.head_dim == 128)
         hipLaunchKernelGGL((pa_decode_stream_kernel<128>), pgrid, dim3(64 * NW), lds2, a.stream, p, (int)items);
       else
@@ -579,7 +669,14 @@ int pa_launch_decode_bf16(const pa_decode_args& a) {
     }
   }
   dim3 grid((uint32_t)a.n_split, (uint32_t)a.hkv, (uint32_t)a.batch);
-  const size_t lds = (size_t)NW * p.G * a.head_dim * sizeof(float);   // at most 64 KB (G <= 16, D <= 128)
+  const size_t lds = a.head_dim == 128 ? dec_o_bytes<128>(p.G) : dec_o_bytes<64>(p.G);   // at most 72 KB (G <= 16)
+  {
+    static std::atomic<unsigned long long> attr_done[2];
+    const int which = a.head_dim == 128 ? 0 : 1;
+    const void* fn = which == 0 ? reinterpret_cast<const void*>(&pa_decode_kernel<128>)
+                                : reinterpret_cast<const void*>(&pa_decode_kernel<64>);
+    if (int st = pa_allow_dynamic_lds(fn, which == 0 ? dec_o_bytes<128>(MAXG) : dec_o_bytes<64>(MAXG), attr_done[which])) return st;
+  }
   if (a.head_dim == 128)
     hipLaunchKernelGGL((pa_decode_kernel<128>), grid, dim3(64 * NW), lds, a.stream, p);
   else
@@ -593,4 +690,3 @@ int pa_launch_decode_bf16(const pa_decode_args& a) {
     hipLaunchKernelGGL((pa_decode_merge_kernel<64>), mgrid, dim3(64), 0, a.stream, p);
   return pa_note_hip(hipGetLastError());
 }
-

@@ -108,9 +108,8 @@ def test_full_size_config4():
         assert np.abs(lse[b:b + 1].double().cpu().numpy() - ol).max() <= 1e-3
 
 
-def test_many_sequences_take_the_two_kernel_merge():
-    # more (sequence, KV head) pairs than the library keeps arrival counters for: the partials are merged by
-    # the second kernel instead of the last workgroup; sequences are checked at both ends and in the middle
+def test_many_sequences():
+    # 4160 (sequence, KV head) pairs of two workgroups each; sequences are checked at both ends and in the middle
     pat = pa.Pattern(64, 4, 1)
     batch, hq, hkv, cap, d = 520, 8, 8, 4096, 128
     g = torch.Generator(device="cuda"); g.manual_seed(35)
@@ -129,8 +128,8 @@ def test_many_sequences_take_the_two_kernel_merge():
 
 
 def test_back_to_back_calls_on_one_workspace():
-    # the arrival counters of the fused merge must be back at zero after every call, and a call must not see
-    # partials of the one before: alternate two different inputs many times and compare with fresh results
+    # a call must not take the partials that the call before left in the workspace for its own (they carry the
+    # previous generation number): alternate two different inputs many times and compare with fresh results
     pat = pa.Pattern(64, 4, 1)
     batch, hq, hkv, cap, d = 4, 8, 2, 8192, 128
     qa, ka, va = synth.decode_inputs(batch, hq, hkv, cap, d, "bf16", 36)
@@ -145,6 +144,49 @@ def test_back_to_back_calls_on_one_workspace():
     for i in range(40):
         o, _ = pa.decode(pat, *(A if i % 2 == 0 else Bt), lens, workspace=ws)
         assert torch.equal(o, ref_a if i % 2 == 0 else ref_b), i
+
+
+def test_many_calls_in_flight_on_several_streams():
+    # 96 calls on four streams, each call with a workspace of its own (calls that may overlap must not share
+    # one; beyond that the library sets no limit on calls in flight): every output equals the one computed alone,
+    # which is checked against the oracle.
+    pat = pa.Pattern(64, 4, 1)
+    batch, hq, hkv, cap, d = 3, 8, 2, 8192, 128
+    cases = []
+    for seed, lens in ((81, [8192, 5000, 64]), (82, [8191, 4097, 1]), (83, [6000, 8192, 129])):
+        q, k, v = synth.decode_inputs(batch, hq, hkv, cap, d, "bf16", seed)
+        oo, olse = orc.decode(synth.to_numpy_storage(q), synth.to_numpy_storage(k), synth.to_numpy_storage(v),
+                              np.asarray(lens), oracle_pattern(pat), None)
+        dev = [t.cuda() for t in (q, k, v, torch.tensor(lens, dtype=torch.int32))]
+        o, lse = pa.decode(pat, *dev)
+        torch.cuda.synchronize()
+        assert np.abs(o.double().cpu().numpy() - oo).max() <= TOL_O["bf16"]
+        assert np.abs(lse.double().cpu().numpy() - olse).max() <= TOL_LSE
+        cases.append((dev, o.clone(), lse.clone()))
+    streams = [torch.cuda.Stream() for _ in range(4)]
+    n_calls = 96
+    wss = [pa.decode_workspace(pat, batch, hq, hkv, d, cap) for _ in range(n_calls)]
+    for i, w in enumerate(wss):
+        w.fill_(i & 0xFF)               # whatever a fresh allocation may hold
+    torch.cuda.synchronize()
+    outs = []
+    for i in range(n_calls):
+        dev, _, _ = cases[i % 3]
+        st = streams[i % 4]
+        with torch.cuda.stream(st):
+            outs.append(pa.decode(pat, *dev, workspace=wss[i], stream=st))
+    torch.cuda.synchronize()
+    for i, (o, lse) in enumerate(outs):
+        _, ro, rl = cases[i % 3]
+        assert torch.equal(o, ro) and torch.equal(lse, rl), i
+
+
+def test_more_splits_than_the_workgroups_merge_among_themselves():
+    # one sequence and a long row: with 21 and 75 workgroups per (sequence, KV head) the partials are left as plain
+    # numbers for the merge kernel; with 10 the workgroups merge among themselves in two rounds of loads
+    for B, W, cap in ((64, 40, 8192), (64, 150, 16384)):
+        run_decode(pa.Pattern(B, W, 1), 1, 4, 1, cap, 128, [cap], seed=84, calls=2)
+    run_decode(pa.Pattern(128, 4, 1), 1, 8, 2, 16384, 128, [16384], seed=85, calls=3)
 
 
 @pytest.mark.parametrize("B,W,S,hq,hkv,d,cap,batch", [
