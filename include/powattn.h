@@ -220,6 +220,27 @@ int powattn_decode(const powattn_pattern* pattern,
                    void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * powattn_decode for callers that cannot allocate device memory for a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * allocation).  Same arguments and result as powattn_decode, without the
+ * workspace: the partial results go to a buffer of POWATTN_STATIC_SCRATCH_BYTES
+ * bytes that the library holds in its own device memory on every GPU it runs on,
+ * from the time it is loaded until the process ends.  The call allocates and
+ * frees nothing.  A shape whose powattn_decode_workspace_bytes(...) exceeds that
+ * size is refused with POWATTN_WORKSPACE_TOO_SMALL before anything is launched.
+ * All calls on one GPU share the one buffer: calls that may overlap in time on
+ * the same GPU (different streams) race and must be serialised by the caller.
+ * Errors: INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR.
+ */
+#define POWATTN_STATIC_SCRATCH_BYTES (32u << 20)
+int powattn_decode_static(const powattn_pattern* pattern,
+                          const void* q, const void* k_cache, const void* v_cache,
+                          const int32_t* d_kv_len, int64_t cache_capacity,
+                          void* o, float* lse,
+                          int32_t batch, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                          int32_t dtype, float softmax_scale, void* hip_stream);
+
+/*
  * powattn_decode over a paged KV cache, the form serving systems keep their
  * caches in (Section 4.3 measures prefill plus 1024 decode steps end to end).
  * A page holds one block of the pattern (pattern->block tokens) for every KV

@@ -24,7 +24,7 @@ EXPORTS = (
     "powattn_version", "powattn_strerror", "powattn_num_blocks", "powattn_max_k",
     "powattn_row_host", "powattn_mask_build", "powattn_prefill",
     "powattn_prefill_chunk", "powattn_prefill_varlen", "powattn_decode_workspace_bytes", "powattn_decode",
-    "powattn_decode_paged", "powattn_backward_workspace_bytes", "powattn_backward",
+    "powattn_decode_static", "powattn_decode_paged", "powattn_backward_workspace_bytes", "powattn_backward",
 )
 
 
@@ -90,6 +90,8 @@ def lib() -> ctypes.CDLL:
     L.powattn_decode.restype = ctypes.c_int
     L.powattn_decode.argtypes = [P, vp, vp, vp, vp, i64, vp, vp, i32, i32, i32, i32, i32, f32,
                                  vp, ctypes.c_size_t, vp]
+    L.powattn_decode_static.restype = ctypes.c_int
+    L.powattn_decode_static.argtypes = [P, vp, vp, vp, vp, i64, vp, vp, i32, i32, i32, i32, i32, f32, vp]
     L.powattn_decode_paged.restype = ctypes.c_int
     L.powattn_decode_paged.argtypes = [P, vp, vp, vp, i64, vp, i32, vp, vp, vp, i32, i32, i32, i32, i32, f32,
                                        vp, ctypes.c_size_t, vp]
@@ -268,6 +270,24 @@ def decode(pattern: Pattern, q, k_cache, v_cache, kv_len, o=None, lse=None, soft
                               float(softmax_scale), _ptr(workspace), workspace.numel() * workspace.element_size(),
                               _stream(stream))
     _check(st, "powattn_decode")
+    return o, lse
+
+
+def decode_static(pattern: Pattern, q, k_cache, v_cache, kv_len, o, lse=None, softmax_scale=0.0, stream=None):
+    """powattn_decode_static: powattn_decode on the library's own scratch buffer.  The caller passes every
+    tensor, o (and lse, if wanted) included: nothing is allocated here or in the library.  Returns (o, lse)."""
+    batch, hq, d = q.shape
+    hkv, cap = k_cache.shape[1], k_cache.shape[2]
+    if k_cache.shape != (batch, hkv, cap, d) or v_cache.shape != k_cache.shape:
+        raise ValueError("cache shape mismatch")
+    if kv_len.dtype != torch.int32 or kv_len.shape != (batch,):
+        raise ValueError("kv_len must be int32 [batch]")
+    if o.shape != q.shape or o.dtype != q.dtype:
+        raise ValueError("o must have the shape and dtype of q")
+    st = lib().powattn_decode_static(ctypes.byref(pattern.c()), _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(kv_len),
+                                     cap, _ptr(o), _ptr(lse), batch, hq, hkv, d, _dtype_code(q),
+                                     float(softmax_scale), _stream(stream))
+    _check(st, "powattn_decode_static")
     return o, lse
 
 

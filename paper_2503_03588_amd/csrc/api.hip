@@ -225,10 +225,11 @@ extern "C" size_t powattn_decode_workspace_bytes(const powattn_pattern* pattern,
 }
 
 // The three decode entry points share everything but where the cache and the workspace come from.
+// use_scratch: the library's static buffer instead of a caller's workspace.
 static int decode_common(const powattn_pattern* pattern, const void* q, const void* k, const void* v,
                          const int32_t* d_kv_len, int64_t capacity, void* o, float* lse,
                          int32_t batch, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
-                         int32_t dtype, float softmax_scale, void* workspace, size_t workspace_bytes,
+                         int32_t dtype, float softmax_scale, void* workspace, size_t workspace_bytes, bool use_scratch,
                          const int32_t* block_table, int32_t table_stride, int64_t n_pages, void* hip_stream) {
   if (!(softmax_scale == softmax_scale)) return POWATTN_INVALID_ARG;
   if (dtype != POWATTN_BF16) return POWATTN_UNSUPPORTED;
@@ -239,6 +240,12 @@ static int decode_common(const powattn_pattern* pattern, const void* q, const vo
   if (powattn_num_blocks(pattern, capacity) < 0) return POWATTN_INVALID_ARG;
   size_t need = powattn_decode_workspace_bytes(pattern, batch, n_q_heads, n_kv_heads, head_dim, capacity);
   if (need == 0) return POWATTN_INVALID_ARG;
+  if (use_scratch) {
+    // sizes are checked against the stated maximum before the device is touched
+    if (need > (size_t)POWATTN_STATIC_SCRATCH_BYTES) return POWATTN_WORKSPACE_TOO_SMALL;
+    int st = pa_decode_scratch(&workspace, &workspace_bytes);
+    if (st != POWATTN_OK) return st;
+  }
   if (!workspace || workspace_bytes < need) return POWATTN_WORKSPACE_TOO_SMALL;
   if (((uintptr_t)workspace & 255u) != 0) return POWATTN_INVALID_ARG;
 
@@ -268,7 +275,22 @@ extern "C" int powattn_decode(const powattn_pattern* pattern,
   if (batch < 1 || n_q_heads < 1 || n_kv_heads < 1 || head_dim < 1 || cache_capacity < 1) return POWATTN_INVALID_ARG;
   if (n_q_heads % n_kv_heads != 0) return POWATTN_INVALID_ARG;
   return decode_common(pattern, q, k_cache, v_cache, d_kv_len, cache_capacity, o, lse, batch, n_q_heads, n_kv_heads,
-                       head_dim, dtype, softmax_scale, workspace, workspace_bytes, nullptr, 0, 0, hip_stream);
+                       head_dim, dtype, softmax_scale, workspace, workspace_bytes, false, nullptr, 0, 0, hip_stream);
+}
+
+extern "C" int powattn_decode_static(const powattn_pattern* pattern,
+                                     const void* q, const void* k_cache, const void* v_cache,
+                                     const int32_t* d_kv_len, int64_t cache_capacity,
+                                     void* o, float* lse,
+                                     int32_t batch, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                                     int32_t dtype, float softmax_scale, void* hip_stream) {
+  int st = pa_check_pattern(pattern);
+  if (st != POWATTN_OK) return st;
+  if (!q || !k_cache || !v_cache || !d_kv_len || !o) return POWATTN_INVALID_ARG;
+  if (batch < 1 || n_q_heads < 1 || n_kv_heads < 1 || head_dim < 1 || cache_capacity < 1) return POWATTN_INVALID_ARG;
+  if (n_q_heads % n_kv_heads != 0) return POWATTN_INVALID_ARG;
+  return decode_common(pattern, q, k_cache, v_cache, d_kv_len, cache_capacity, o, lse, batch, n_q_heads, n_kv_heads,
+                       head_dim, dtype, softmax_scale, nullptr, 0, true, nullptr, 0, 0, hip_stream);
 }
 
 extern "C" int powattn_decode_paged(const powattn_pattern* pattern,
@@ -286,7 +308,7 @@ extern "C" int powattn_decode_paged(const powattn_pattern* pattern,
   if (n_q_heads % n_kv_heads != 0) return POWATTN_INVALID_ARG;
   const int64_t capacity = (int64_t)table_stride * pattern->block;      // tokens a sequence's table can hold
   return decode_common(pattern, q, k_pages, v_pages, d_kv_len, capacity, o, lse, batch, n_q_heads, n_kv_heads,
-                       head_dim, dtype, softmax_scale, workspace, workspace_bytes,
+                       head_dim, dtype, softmax_scale, workspace, workspace_bytes, false,
                        d_block_table, table_stride, n_pages, hip_stream);
 }
 

@@ -60,6 +60,8 @@ int pa_launch_decode_bf16(const pa_decode_args& a);
 // total workspace bytes of a decode call with n_split workgroups per (sequence, KV head); *header_bytes (may be
 // null) receives the size of the generation numbers at its start
 size_t pa_decode_workspace_layout(int32_t batch, int32_t hq, int32_t hkv, int32_t head_dim, int32_t n_split, size_t* header_bytes);
+// the library's static scratch buffer on the current device: its device address and size
+int pa_decode_scratch(void** ptr_out, size_t* bytes_out);
 
 struct pa_backward_args {
   powattn_pattern pat;

@@ -618,6 +618,28 @@ size_t pa_decode_workspace_layout(int32_t batch, int32_t hq, int32_t hkv, int32_
   return hdr + ((partials + 255) & ~(size_t)255);
 }
 
+// ---- the library's own scratch buffer, for callers that cannot allocate a workspace ----
+// One array per GPU, held until the process ends; its address on a device is looked up once, with that device
+// current, and kept.  The array's name is a host-side handle only: device code and HIP calls get the looked-up
+// pointer.  Zero when the module is loaded, which the merge protocol above does not even need.
+static __device__ __align__(256) unsigned char scratch[POWATTN_STATIC_SCRATCH_BYTES];
+
+int pa_decode_scratch(void** ptr_out, size_t* bytes_out) {
+  static std::atomic<void*> dev_ptr[64];           // per device; null = not looked up yet
+  int dev = 0;
+  pa_current_device(&dev, nullptr);
+  void* ptr = dev_ptr[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return pa_note_hip(e);
+    if (!ptr) return pa_note_hip(hipErrorInvalidSymbol);
+    dev_ptr[dev].store(ptr, std::memory_order_release);   // threads that race here store the same address
+  }
+  *ptr_out = ptr;
+  *bytes_out = sizeof(scratch);
+  return POWATTN_OK;
+}
+
 int pa_launch_decode_bf16(const pa_decode_args& a) {
   if (a.n_split < 1) return POWATTN_UNSUPPORTED;
   if (a.hkv > 65535 || a.batch > 65535 || a.hq > 65535 * 16) return POWATTN_UNSUPPORTED;

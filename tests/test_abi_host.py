@@ -178,6 +178,25 @@ def test_decode_argument_errors(L):
     assert _decode(L, ws=FAKE + 8) == pa.INVALID_ARG                          # misaligned workspace
 
 
+def test_decode_static_argument_errors_are_found_before_the_device_is_touched(L):
+    def call(pat=None, q=FAKE, k=FAKE, v=FAKE, kv_len=FAKE, cap=65536, o=FAKE, batch=2, hq=8, hkv=2, d=128,
+             dtype=pa.BF16, scale=0.0):
+        cp = (pat or pa.Pattern(64, 4, 1)).c()
+        return L.powattn_decode_static(ctypes.byref(cp), q, k, v, kv_len, cap, o, None, batch, hq, hkv, d, dtype,
+                                       scale, None)
+    assert call(q=None) == pa.INVALID_ARG
+    assert call(kv_len=None) == pa.INVALID_ARG
+    assert call(o=None) == pa.INVALID_ARG
+    assert call(cap=0) == pa.INVALID_ARG
+    assert call(hq=6, hkv=4) == pa.INVALID_ARG
+    assert call(d=80) == pa.UNSUPPORTED
+    assert call(dtype=pa.F32) == pa.UNSUPPORTED
+    assert call(scale=float("nan")) == pa.INVALID_ARG
+    # a shape whose partial results do not fit the library's static buffer (32 MiB) is refused
+    assert pa.decode_workspace_bytes(pa.Pattern(64, 4, 1), 1024, 32, 8, 128, 65536) > (32 << 20)
+    assert call(batch=1024, hq=32, hkv=8) == pa.WORKSPACE_TOO_SMALL
+
+
 def _paged(L, pat=None, q=FAKE, k=FAKE, v=FAKE, n_pages=100, table=FAKE, stride=64, kv_len=FAKE, o=FAKE, lse=None,
            batch=2, hq=8, hkv=2, d=128, dtype=pa.BF16, scale=0.0, ws=FAKE, ws_bytes=None):
     p = pat or pa.Pattern(64, 4, 1)
