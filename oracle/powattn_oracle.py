@@ -1,4 +1,4 @@
-"""CPU float64 oracle for PowerAttention's forward pass.  TEST INFRASTRUCTURE ONLY.
+"""CPU float64 oracle for PowerAttention's forward pass and its gradients.  TEST INFRASTRUCTURE ONLY.
 
 This module is the slow, plain definition that the GPU library is checked
 against.  It is imported by the tests, by the smoke check and by the bench's
@@ -337,6 +337,43 @@ def backward_sample(q, k, v, do, rows, keys, pat: Pattern, scale=None):
                 dsk = pk * (do[b, h, qs] @ vh[keys].T - delta)
                 dk[b, h // g] += scale * (dsk.T @ q[b, h, qs])
                 dv[b, h // g] += pk.T @ do[b, h, qs]
+    return dq, dk, dv
+
+
+def attention_backward_rows(q, k, v, do_rows, rows, pat: Pattern, scale=None):
+    """The gradients of `attention_backward` for an upstream gradient dO that is zero outside the query
+    positions `rows` (do_rows: [batch, Hq, len(rows), D] holds its rows there).
+
+    A query row with dO = 0 has dP = 0 and rowsum(P * dP) = 0, hence dS = 0: it contributes nothing to dQ, dK
+    or dV.  So the sums over queries in dK = scale * dS^T Q and dV = P^T dO run over `rows` only, and each of
+    those rows is the dense, masked row of Equation 1 against all keys, exactly as in `attention_backward`.
+    That keeps sequences far too long for the N x N form within reach, for every key at once (the sink
+    blocks' keys included, which every later query attends).
+    Returns dq [batch, Hq, len(rows), D] (the other rows of dQ are zero), dk, dv [batch, Hkv, N, D].
+    """
+    q, k, v, do_rows = widen(q), widen(k), widen(v), widen(do_rows)
+    batch, hq, n, d = q.shape
+    hkv = k.shape[1]
+    g = hq // hkv
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    rows = np.asarray(rows, dtype=np.int64)
+    allowed = token_mask_rows(rows, n, pat)
+    dq = np.zeros((batch, hq, rows.size, d))
+    dk = np.zeros_like(k)
+    dv = np.zeros_like(v)
+    for b in range(batch):
+        for h in range(hq):
+            kh, vh = k[b, h // g], v[b, h // g]
+            qr = q[b, h, rows]
+            s = np.where(allowed, scale * (qr @ kh.T), -np.inf)
+            p = np.exp(s - s.max(axis=1, keepdims=True))
+            p /= p.sum(axis=1, keepdims=True)
+            dp = do_rows[b, h] @ vh.T
+            ds = p * (dp - (p * dp).sum(axis=1, keepdims=True))
+            dq[b, h] = scale * (ds @ kh)
+            dk[b, h // g] += scale * (ds.T @ qr)
+            dv[b, h // g] += p.T @ do_rows[b, h]
     return dq, dk, dv
 
 

@@ -152,3 +152,30 @@ def test_sampled_form_equals_the_dense_form():
         assert np.abs(sk - dk[:, :, keys]).max() < 1e-12
         assert np.abs(sv - dv[:, :, keys]).max() < 1e-12
 
+
+
+def test_row_sparse_form_equals_the_dense_form_with_do_zero_elsewhere():
+    # attention_backward_rows is pinned to attention_backward (itself pinned by finite differences and autograd):
+    # with dO zero outside the sampled rows the dense form must give the same dK, dV for EVERY key and the same
+    # dQ on the rows, and exactly zero dQ elsewhere; and autograd through a library softmax agrees as well
+    batch, hq, hkv, n, d = 2, 4, 2, 150, 8
+    q, k, v = _rand((batch, hq, n, d), 34), _rand((batch, hkv, n, d), 35), _rand((batch, hkv, n, d), 36)
+    rows = np.array([0, 7, 8, 63, 64, 100, 149])
+    do = np.zeros((batch, hq, n, d))
+    do[:, :, rows] = _rand((batch, hq, rows.size, d), 37)
+    for pat in (Pattern(8, 2, 1), Pattern(16, 3, 0), Pattern(8, 2, 2, power=False)):
+        dq, dk, dv = orc.attention_backward(q, k, v, do, pat, 0.3)
+        rq, rk, rv = orc.attention_backward_rows(q, k, v, do[:, :, rows], rows, pat, 0.3)
+        assert np.abs(rq - dq[:, :, rows]).max() < 1e-12
+        assert np.abs(rk - dk).max() < 1e-12 and np.abs(rv - dv).max() < 1e-12
+        others = np.setdiff1d(np.arange(n), rows)
+        assert (dq[:, :, others] == 0).all()
+    pat = Pattern(8, 2, 1)
+    tq, tk, tv = (torch.from_numpy(x).clone().requires_grad_(True) for x in (q, k, v))
+    mask = torch.from_numpy(orc.token_mask(n, pat))
+    s = (tq @ tk.repeat_interleave(2, dim=1).transpose(-1, -2)) / math.sqrt(d)
+    o = torch.softmax(s.masked_fill(~mask, float("-inf")), dim=-1) @ tv.repeat_interleave(2, dim=1)
+    (o * torch.from_numpy(do)).sum().backward()
+    rq, rk, rv = orc.attention_backward_rows(q, k, v, do[:, :, rows], rows, pat)
+    assert np.abs(rq - tq.grad.numpy()[:, :, rows]).max() < 1e-12
+    assert np.abs(rk - tk.grad.numpy()).max() < 1e-12 and np.abs(rv - tv.grad.numpy()).max() < 1e-12
