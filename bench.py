@@ -7,14 +7,20 @@ One "step" = one pass of the method's path over one batch of synthetic input:
     head_dim 128, seq 131072, block 128, window 4, sink 1, bf16 N(0,1))
   + one decode step (configuration 4: batch 16, 32/8 heads, 65536-token bf16 caches,
     block 64, window 4, sink 1), rotating over several distinct caches so the reads come from HBM.
-The in-library dense causal kernel (the comparison leg) and the CPU oracle are timed outside
-the timed region.  Prints ONE JSON line.
+Everything else is timed outside that region and reported next to it: every prefill configuration with and
+without the sink block, the tiny fp32 configuration, decode at 64K and 128K caches and at larger batches, the
+in-library dense causal kernel, the paper's own setting over 16K-128K, the 28-layer stack, the backward pass,
+the machine's measured ceilings, the clock and power the prefill kernel sustains, and the CPU oracle (which
+doubles as the bench's own parity check of what it timed).  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--no-dense] [--no-sustained]
+                  [--no-measured-peaks]
 """
 import argparse
 import json
 import os
+import statistics
+import subprocess
 import sys
 import time
 
@@ -25,23 +31,33 @@ if ROOT not in sys.path:
 PEAK_MFMA_BF16_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E peak
 
-# HBM traffic of one prefill launch at the default workload, from rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE runs scaled by a copy kernel of known size (profiles/prefill_bf16_128k_pmc.md).
-# read 4.33 GB + written 1.09 GB per launch.
-PREFILL_TRAFFIC_BYTES = 5.43e9
-# The same for one decode launch at the default workload (profiles/decode_b16_64k_pmc.md):
-# read 55.5 MB (the partials that the merging workgroups read back included) + written 0.79 MB.
-DECODE_TRAFFIC_BYTES = 56.3e6
+# HBM traffic per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, scaled by a copy kernel of known
+# size.  Counters cannot be read from inside this program, so each figure is stamped with the library version,
+# the kernel and the grid it was taken on (profiles/*.md hold the runs); it is reported only while the library
+# that is loaded still has that version (the version number moves with every change to a kernel), else null.
+TRAFFIC = {
+    "prefill": {"bytes": 5.43e9, "library_version": 100, "kernel": "pa_prefill_bf16_kernel<128,8,4,false,true>",
+                "grid": 256, "source": "profiles/prefill_bf16_128k_pmc.md"},
+    "decode": {"bytes": 56.3e6, "library_version": 100, "kernel": "pa_decode_kernel<128>", "grid": [2, 8, 16],
+               "source": "profiles/decode_b16_64k_pmc.md"},
+}
+
+
+def stats(samples):
+    """mean / median / min of a list of per-launch times."""
+    return {"mean": round(statistics.fmean(samples), 5), "median": round(statistics.median(samples), 5),
+            "min": round(min(samples), 5), "n": len(samples)}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-sustained", action="store_true")
+    ap.add_argument("--no-measured-peaks", action="store_true")
     ap.add_argument("--dense-iters", type=int, default=2)
     ap.add_argument("--decode-caches", type=int, default=6)
     ap.add_argument("--cpu-rows", type=int, default=512)
@@ -63,6 +79,40 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dev = "cuda"
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def time_launches(fn, iters, warm=20):
+        """Per-launch times in ms: every launch between its own pair of events on the launch stream."""
+        for s in range(warm):
+            fn(s)
+        torch.cuda.synchronize()
+        marks = [(ev(), ev()) for _ in range(iters)]
+        for s in range(iters):
+            marks[s][0].record()
+            fn(s)
+            marks[s][1].record()
+        torch.cuda.synchronize()
+        return [a.elapsed_time(b) for a, b in marks]
+
+    def time_batches(fn, per_batch, batches, warm=24):
+        """For launches of a few microseconds an event pair per launch would be most of what is measured: times
+        batches of back-to-back launches and returns microseconds per launch, one figure per batch."""
+        for s in range(warm):
+            fn(s)
+        torch.cuda.synchronize()
+        marks = [(ev(), ev()) for _ in range(batches)]
+        s = 0
+        for bi in range(batches):
+            marks[bi][0].record()
+            for _ in range(per_batch):
+                fn(s)
+                s += 1
+            marks[bi][1].record()
+        torch.cuda.synchronize()
+        return [a.elapsed_time(b) * 1e3 / per_batch for a, b in marks]
+
+    def flops_block(B, d, hq, batch, pairs):
+        return 4.0 * B * B * d * hq * batch * pairs          # attended blocks only, the diagonal block counted whole
 
     # ---------------- workload ----------------
     P = dict(batch=1, hq=32, hkv=8, n=131072, d=128, B=128, W=4, S=1, seed=2)          # configuration 3
@@ -97,8 +147,6 @@ def main():
     lsed = torch.empty((Dc["batch"], Dc["hq"]), dtype=torch.float32, device=dev)
     ws = pa.decode_workspace(pat_d, Dc["batch"], Dc["hq"], Dc["hkv"], Dc["d"], Dc["cap"])
 
-    ev = lambda: torch.cuda.Event(enable_timing=True)
-
     def step(s, marks=None):
         pa.mask_build(pat_p, P["n"], kv_cnt=cnt, kv_idx=idx)
         if marks is not None:
@@ -118,6 +166,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # ---------------- the timed region ----------------
     for s in range(args.warmup):
         step(s)
     torch.cuda.synchronize()
@@ -128,23 +177,76 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    prefill_ms = sum(m[0].elapsed_time(m[1]) for m in marks) / args.steps
-    decode_in_step_us = sum(m[1].elapsed_time(m[2]) for m in marks) / args.steps * 1e3
+    prefill_samples = [m[0].elapsed_time(m[1]) for m in marks]
+    prefill_ms = statistics.fmean(prefill_samples)
+    decode_in_step = [m[1].elapsed_time(m[2]) * 1e3 for m in marks]
+    decode_in_step_us = statistics.fmean(decode_in_step)
 
-    # Decode as it runs in generation: step after step, each on another cache so that every read is cold.
-    # (Inside the step above the decode launch follows a 3 ms prefill and an event record; that figure is
-    # reported too, as in_step_us.)
-    dec_iters = 20 * len(caches)
-    for s in range(2 * len(caches)):
-        pa.decode(pat_d, qd, *caches[s % len(caches)], lens, o=od, lse=lsed, workspace=ws)
-    torch.cuda.synchronize()
-    d0, d1 = ev(), ev()
-    d0.record()
-    for s in range(dec_iters):
-        pa.decode(pat_d, qd, *caches[s % len(caches)], lens, o=od, lse=lsed, workspace=ws)
-    d1.record()
-    torch.cuda.synchronize()
-    decode_us = d0.elapsed_time(d1) * 1e3 / dec_iters
+    pairs = int(cnt.sum().item())
+    f_block = flops_block(P["B"], P["d"], P["hq"], P["batch"], pairs)
+    value = f_block / (ms_per_step * 1e-3) / 1e12
+    prefill_tflops = f_block / (prefill_ms * 1e-3) / 1e12
+    lib_version = pa.version()
+
+    def traffic(which):
+        t = TRAFFIC[which]
+        return dict(t) if t["library_version"] == lib_version else None
+
+    # ---------------- every prefill configuration, with and without the sink block (Section 4.4 measures the
+    # kernel alone over context lengths; the sink is a parameter here, the paper's pattern has one block) ----------
+    configs = []
+    prefill_cfgs = [
+        ("2", dict(hq=32, hkv=8, n=32768, d=128, B=64, W=4, seed=1)),
+        ("3", dict(hq=32, hkv=8, n=131072, d=128, B=128, W=4, seed=2)),
+        ("5 (one layer)", dict(hq=28, hkv=4, n=65536, d=128, B=64, W=4, seed=4000)),
+    ]
+    for name, c in prefill_cfgs:
+        if name == "3":
+            qc, kc_, vc_ = qg, kg, vg
+        else:
+            gl = torch.Generator(device=dev)
+            gl.manual_seed(c["seed"])
+            qc = torch.randn(1, c["hq"], c["n"], c["d"], device=dev, dtype=torch.bfloat16, generator=gl)
+            kc_ = torch.randn(1, c["hkv"], c["n"], c["d"], device=dev, dtype=torch.bfloat16, generator=gl)
+            vc_ = torch.randn(1, c["hkv"], c["n"], c["d"], device=dev, dtype=torch.bfloat16, generator=gl)
+        oc = torch.empty_like(qc)
+        lsec = torch.empty((1, c["hq"], c["n"]), dtype=torch.float32, device=dev)
+        for S in (1, 0):
+            pat_c = pa.Pattern(c["B"], c["W"], S)
+            c_c, i_c, _ = pa.mask_build(pat_c, c["n"])
+            ms = time_launches(lambda s: pa.prefill(pat_c, c_c, i_c, qc, kc_, vc_, o=oc, lse=lsec), 50, 20)
+            prs = int(c_c.sum().item())
+            fb = flops_block(c["B"], c["d"], c["hq"], 1, prs)
+            st = stats(ms)
+            configs.append({"configuration": name, "sink_blocks": S,
+                            "shape": f"b1, {c['hq']}q/{c['hkv']}kv, N={c['n']}, D={c['d']}, block {c['B']}, W={c['W']}, bf16",
+                            "attended_block_pairs": prs, "flops": fb, "kernel_ms": st,
+                            "tflops": round(fb / (st["mean"] * 1e-3) / 1e12, 1),
+                            "tflops_at_min": round(fb / (st["min"] * 1e-3) / 1e12, 1),
+                            "frac_of_mfma_peak": round(fb / (st["mean"] * 1e-3) / 1e12 / PEAK_MFMA_BF16_TFLOPS, 4)})
+        del oc, lsec
+        if name != "3":
+            del qc, kc_, vc_
+    # configuration 1 (tiny fp32 parity configuration): launch-latency sized, time only
+    q1, k1, v1 = (t.to(dev) for t in synth.qkv(1, 2, 2, 1024, 64, "f32", seed=0))
+    pat_1 = pa.Pattern(64, 2, 1)
+    c_1, i_1, _ = pa.mask_build(pat_1, 1024)
+    o1 = torch.empty_like(q1)
+    l1 = torch.empty((1, 2, 1024), dtype=torch.float32, device=dev)
+    us1 = time_batches(lambda s: pa.prefill(pat_1, c_1, i_1, q1, k1, v1, o=o1, lse=l1), 20, 10)
+    configs.append({"configuration": "1", "sink_blocks": 1, "shape": "b1, 2 heads, N=1024, D=64, block 64, W=2, fp32",
+                    "attended_block_pairs": int(c_1.sum().item()), "kernel_us": stats(us1),
+                    "note": "fp32 FMA kernel, 1.6e8 flop: bound by launch latency, time only"})
+
+    # ---------------- decode as it runs in generation: step after step, each on another cache so that every
+    # read is cold.  (Inside the step above the decode launch follows a 3 ms prefill and an event record; that
+    # figure is reported too, as in_step_us.) ----------------
+    dec_samples = time_batches(lambda s: pa.decode(pat_d, qd, *caches[s % len(caches)], lens, o=od, lse=lsed, workspace=ws),
+                               20, 12, warm=4 * len(caches))
+    decode_us = statistics.fmean(dec_samples)
+    row = pa.row_host(pat_d, (Dc["len"] - 1) // Dc["B"])
+    decode_bytes = len(row) * Dc["B"] * Dc["d"] * 2 * 2 * Dc["hkv"] * Dc["batch"]   # attended K and V tokens
+    decode_gbs = decode_bytes / (decode_us * 1e-6) / 1e9
 
     # The same step over a paged cache (powattn_decode_paged): the caches' memory read as a pool of pages of one
     # block each, every sequence's blocks on random pages of the whole pool (26 GB: cold), several tables in
@@ -153,7 +255,7 @@ def main():
     kpool = kall.view(-1, Dc["hkv"], Dc["B"], Dc["d"])
     vpool = vall.view(-1, Dc["hkv"], Dc["B"], Dc["d"])
     n_pages, stride = kpool.shape[0], Dc["cap"] // Dc["B"]
-    n_row = len(pa.row_host(pat_d, (Dc["len"] - 1) // Dc["B"]))
+    n_row = len(row)
     paged = []
     for batch in (Dc["batch"], 64, 256):
         tables = [torch.randint(0, n_pages, (batch, stride), dtype=torch.int32, device=dev, generator=gen)
@@ -163,31 +265,63 @@ def main():
         ob = torch.empty_like(qb)
         lseb = torch.empty((batch, Dc["hq"]), dtype=torch.float32, device=dev)
         wsb = pa.decode_workspace(pat_d, batch, Dc["hq"], Dc["hkv"], Dc["d"], Dc["cap"])
-        iters = 80
-        for s in range(8):
-            pa.decode_paged(pat_d, qb, kpool, vpool, tables[s % 4], lb, o=ob, lse=lseb, workspace=wsb)
-        torch.cuda.synchronize()
-        p0, p1 = ev(), ev()
-        p0.record()
-        for s in range(iters):
-            pa.decode_paged(pat_d, qb, kpool, vpool, tables[s % 4], lb, o=ob, lse=lseb, workspace=wsb)
-        p1.record()
-        torch.cuda.synchronize()
-        us = p0.elapsed_time(p1) * 1e3 / iters
+        us = time_batches(lambda s: pa.decode_paged(pat_d, qb, kpool, vpool, tables[s % 4], lb, o=ob, lse=lseb,
+                                                    workspace=wsb), 10, 8, warm=20)
+        st = stats(us)
         nbytes = n_row * Dc["B"] * Dc["d"] * 2 * 2 * Dc["hkv"] * batch
-        paged.append({"batch": batch, "us_per_step": round(us, 2), "tokens_per_s": round(batch / (us * 1e-6), 1),
-                      "GB/s": round(nbytes / (us * 1e-6) / 1e9, 1),
-                      "frac_of_hbm_peak": round(nbytes / (us * 1e-6) / 1e9 / PEAK_HBM_GBS, 4)})
+        paged.append({"batch": batch, "us_per_step": st, "tokens_per_s": round(batch / (st["mean"] * 1e-6), 1),
+                      "GB/s": round(nbytes / (st["mean"] * 1e-6) / 1e9, 1),
+                      "frac_of_hbm_peak": round(nbytes / (st["mean"] * 1e-6) / 1e9 / PEAK_HBM_GBS, 4)})
         del tables, qb, lb, ob, lseb, wsb
 
-    pairs = int(cnt.sum().item())
-    f_block = 4.0 * P["B"] * P["B"] * P["d"] * P["hq"] * P["batch"] * pairs      # attended blocks, diagonal whole
-    value = f_block / (ms_per_step * 1e-3) / 1e12
-    prefill_tflops = f_block / (prefill_ms * 1e-3) / 1e12
+    # decode at a 131072-token context (the metric's "at 128K"): the same 16 sequences with caches twice as long;
+    # a row has one more power-of-two block.  Three caches of 8.6 GB in rotation (cold); freed afterwards.
+    Dl = dict(Dc, len=131072, cap=131072 + 64)
+    k128 = torch.randn(3, Dl["batch"], Dl["hkv"], Dl["cap"], Dl["d"], device=dev, dtype=torch.bfloat16, generator=gen)
+    v128 = torch.randn(3, Dl["batch"], Dl["hkv"], Dl["cap"], Dl["d"], device=dev, dtype=torch.bfloat16, generator=gen)
+    lens128 = torch.full((Dl["batch"],), Dl["len"], dtype=torch.int32, device=dev)
+    ws128 = pa.decode_workspace(pat_d, Dl["batch"], Dl["hq"], Dl["hkv"], Dl["d"], Dl["cap"])
+    us128 = time_batches(lambda s: pa.decode(pat_d, qd, k128[s % 3], v128[s % 3], lens128, o=od, lse=lsed, workspace=ws128),
+                         20, 12, warm=12)
+    row128 = pa.row_host(pat_d, (Dl["len"] - 1) // Dl["B"])
+    bytes128 = len(row128) * Dl["B"] * Dl["d"] * 2 * 2 * Dl["hkv"] * Dl["batch"]
+    st128 = stats(us128)
+    decode_128k = {"context": Dl["len"], "attended_blocks": len(row128), "bytes_per_step": bytes128, "us_per_step": st128,
+                   "tokens_per_s": round(Dl["batch"] / (st128["mean"] * 1e-6), 1),
+                   "GB/s": round(bytes128 / (st128["mean"] * 1e-6) / 1e9, 1),
+                   "frac_of_hbm_peak": round(bytes128 / (st128["mean"] * 1e-6) / 1e9 / PEAK_HBM_GBS, 4)}
+    # kept for the parity check below: sequence 0 of cache 0
+    k128_seq0, v128_seq0 = k128[0, :1].clone(), v128[0, :1].clone()
+    pa.decode(pat_d, qd, k128[0], v128[0], lens128, o=od, lse=lsed, workspace=ws128)
+    torch.cuda.synchronize()
+    od128_seq0, lse128_seq0 = od[:1].clone(), lsed[:1].clone()
+    del k128, v128, ws128
 
-    row = pa.row_host(pat_d, (Dc["len"] - 1) // Dc["B"])
-    decode_bytes = len(row) * Dc["B"] * Dc["d"] * 2 * 2 * Dc["hkv"] * Dc["batch"]   # attended K and V tokens
-    decode_gbs = decode_bytes / (decode_us * 1e-6) / 1e9
+    # ---------------- what this machine can do at most (stand-alone programs built next to the library) -----------
+    measured_peaks = None
+    if not args.no_measured_peaks:
+        measured_peaks = {}
+        bdir = os.path.join(ROOT, "paper_2503_03588_amd", "microbench", "bin")
+        for prog in ("mfma_peak", "stream_decode"):
+            exe = os.path.join(bdir, prog)
+            if not os.path.exists(exe):
+                measured_peaks[prog] = "not built (python -m paper_2503_03588_amd.build)"
+                continue
+            try:
+                out = subprocess.run([exe], capture_output=True, text=True, timeout=120).stdout
+            except Exception as e:                                   # a ceiling is context, not the measurement
+                measured_peaks[prog] = f"failed: {e}"
+                continue
+            for line in out.splitlines():
+                if line.startswith("RESULT "):
+                    for kv in line.split()[1:]:
+                        key, val = kv.split("=")
+                        measured_peaks[key] = float(val)
+        if "mfma_bf16_tflops" in measured_peaks:
+            measured_peaks["prefill_frac_of_measured_mfma"] = round(prefill_tflops / measured_peaks["mfma_bf16_tflops"], 4)
+        if "decode_shaped_read_cold_us" in measured_peaks:
+            measured_peaks["decode_shaped_read_GB/s"] = round(measured_peaks["bytes"] / measured_peaks["decode_shaped_read_cold_us"] / 1e3, 1)
+            measured_peaks["decode_step_over_read_only"] = round(decode_us / measured_peaks["decode_shaped_read_cold_us"], 3)
 
     # ---------------- the clock and the power the prefill kernel sustains (outside the timed region) ----------------
     # The kernel runs back to back for about two seconds while rocm-smi / amd-smi (child processes that only read
@@ -197,7 +331,6 @@ def main():
     sustained = None
     if not args.no_sustained:
         import re
-        import subprocess
         import threading
 
         def tool(cmd):
@@ -254,17 +387,11 @@ def main():
     if not args.no_dense:
         pat_dense = pa.Pattern(P["B"], P["W"], P["S"], flags=pa.DENSE)
         o2 = torch.empty_like(qg)
-        pa.prefill(pat_dense, None, None, qg, kg, vg, o=o2, want_lse=False)
-        torch.cuda.synchronize()
-        e0, e1 = ev(), ev()
-        e0.record()
-        for _ in range(args.dense_iters):
-            pa.prefill(pat_dense, None, None, qg, kg, vg, o=o2, want_lse=False)
-        e1.record()
-        torch.cuda.synchronize()
-        dense_ms = e0.elapsed_time(e1) / args.dense_iters
+        dms = time_launches(lambda s: pa.prefill(pat_dense, None, None, qg, kg, vg, o=o2, want_lse=False),
+                            args.dense_iters, 1)
+        dense_ms = statistics.fmean(dms)
         f_dense = 4.0 * P["d"] * P["hq"] * P["batch"] * (P["n"] * (P["n"] + 1) / 2)
-        dense = {"ms": round(dense_ms, 3), "tflops_causal": round(f_dense / (dense_ms * 1e-3) / 1e12, 1),
+        dense = {"ms": stats(dms), "tflops_causal": round(f_dense / (dense_ms * 1e-3) / 1e12, 1),
                  "speedup_sparse_vs_dense": round(dense_ms / prefill_ms, 2),
                  "block_pair_ratio": round((nb * (nb + 1) / 2) / pairs, 2)}
         del o2
@@ -281,52 +408,52 @@ def main():
             qs, ks_, vs_ = qg[:, :, :n_ctx].contiguous(), kg[:, :, :n_ctx].contiguous(), vg[:, :, :n_ctx].contiguous()
             os_ = torch.empty_like(qs)
             c_s, i_s, _ = pa.mask_build(pat_s, n_ctx)
-
-            def timed(fn, iters):
-                fn()
-                torch.cuda.synchronize()
-                a, b = ev(), ev()
-                a.record()
-                for _ in range(iters):
-                    fn()
-                b.record()
-                torch.cuda.synchronize()
-                return a.elapsed_time(b) / iters
-            ms_s = timed(lambda: pa.prefill(pat_s, c_s, i_s, qs, ks_, vs_, o=os_, want_lse=False), 5)
-            ms_d = timed(lambda: pa.prefill(pat_sd, None, None, qs, ks_, vs_, o=os_, want_lse=False),
-                         3 if n_ctx < 131072 else 1)
+            ms_s = stats(time_launches(lambda s: pa.prefill(pat_s, c_s, i_s, qs, ks_, vs_, o=os_, want_lse=False), 20, 20))
+            ms_d = stats(time_launches(lambda s: pa.prefill(pat_sd, None, None, qs, ks_, vs_, o=os_, want_lse=False),
+                                       3 if n_ctx < 131072 else 1, 1))
             nbs = n_ctx // 256
-            sweep.append({"n": n_ctx, "sparse_ms": round(ms_s, 4), "dense_ms": round(ms_d, 3),
-                          "dense_over_sparse": round(ms_d / ms_s, 2),
+            sweep.append({"n": n_ctx, "sparse_ms": ms_s, "dense_ms": ms_d,
+                          "dense_over_sparse": round(ms_d["mean"] / ms_s["mean"], 2),
                           "block_pair_ratio": round((nbs * (nbs + 1) / 2) / int(c_s.sum().item()), 2)})
             del qs, ks_, vs_, os_
 
-    # ---------------- layer stack (configuration 5): 28 successive sparse-attention layers, 28 query /
-    # 4 KV heads, 64K context, block 64, fresh random Q/K/V per layer (no projection weights exist, so the layers
-    # are not chained); per-layer kernel time.  Second pass: the hybrid schedule of Section 4.3, in which 2 of
-    # every 7 layers keep full attention.  Outside the timed region. ----------------
     # ---------------- gradients (powattn_backward) at the 128K workload: dQ, dK, dV from dO.  FLOPs as the five
     # products of the definition (S, dP, dV, dQ, dK) over the attended block pairs: 2.5 x the forward count; the
     # kernels compute S and dP twice (once per pass), which is not counted. ----------------
     backward = None
+    bwd_parity_inputs = None
     if not args.no_dense:
         dog = torch.randn(qg.shape, device=dev, dtype=torch.bfloat16, generator=gen)
         dqg, dkg, dvg = torch.empty_like(qg), torch.empty_like(kg), torch.empty_like(vg)
         wsb = torch.empty((pa.backward_workspace_bytes(pat_p, P["batch"], P["hq"], P["hkv"], P["n"], P["d"]),),
                           dtype=torch.uint8, device=dev)
-        pa.backward(pat_p, cnt, idx, qg, kg, vg, og, lseg, dog, dq=dqg, dk=dkg, dv=dvg, workspace=wsb)
-        torch.cuda.synchronize()
-        b0, b1 = ev(), ev()
-        b0.record()
-        for _ in range(3):
+        pa.prefill(pat_p, cnt, idx, qg, kg, vg, o=og, lse=lseg)
+        bms = time_launches(lambda s: pa.backward(pat_p, cnt, idx, qg, kg, vg, og, lseg, dog, dq=dqg, dk=dkg, dv=dvg,
+                                                  workspace=wsb), 5, 2)
+        st = stats(bms)
+        backward = {"ms": st, "tflops_5_products": round(2.5 * f_block / (st["mean"] * 1e-3) / 1e12, 1),
+                    "frac_of_mfma_peak": round(2.5 * f_block / (st["mean"] * 1e-3) / 1e12 / PEAK_MFMA_BF16_TFLOPS, 4),
+                    "over_forward": round(st["mean"] / prefill_ms, 2)}
+        if not args.no_cpu_baseline:
+            # For the parity check below: the same launch once more with an upstream gradient that is zero outside
+            # a few query rows, so that the oracle's row-sparse form gives dK and dV of every key (the sink block's
+            # too, which every query attends) from those rows alone.
+            rng_b = np.random.default_rng(777)
+            rows_b = np.unique(np.concatenate([[0, 127, 128, P["n"] - 1], 2048 * np.arange(0, 64, 4) + rng_b.integers(0, 2048, 16),
+                                               rng_b.integers(0, P["n"], 44)]))
+            do_rows = synth.gaussian((1, P["hq"], rows_b.size, P["d"]), "bf16", 778)
+            dog.zero_()
+            dog[:, :, torch.from_numpy(rows_b).to(dev)] = do_rows.to(dev)
             pa.backward(pat_p, cnt, idx, qg, kg, vg, og, lseg, dog, dq=dqg, dk=dkg, dv=dvg, workspace=wsb)
-        b1.record()
-        torch.cuda.synchronize()
-        bms = b0.elapsed_time(b1) / 3
-        backward = {"ms": round(bms, 3), "tflops_5_products": round(2.5 * f_block / (bms * 1e-3) / 1e12, 1),
-                    "over_forward": round(bms / prefill_ms, 2)}
+            torch.cuda.synchronize()
+            bwd_parity_inputs = (rows_b, do_rows, dqg[:, :4].double().cpu().numpy(), dkg[:, :1].double().cpu().numpy(),
+                                 dvg[:, :1].double().cpu().numpy())
         del dog, dqg, dkg, dvg, wsb
 
+    # ---------------- layer stack (configuration 5): 28 successive sparse-attention layers, 28 query /
+    # 4 KV heads, 64K context, block 64, fresh random Q/K/V per layer (no projection weights exist, so the layers
+    # are not chained); per-layer kernel time.  Second pass: the hybrid schedule of Section 4.3, in which 2 of
+    # every 7 layers keep full attention.  Outside the timed region. ----------------
     stack = None
     if not args.no_dense:
         Ls = dict(layers=28, hq=28, hkv=4, n=65536, d=128, B=64, W=4, S=1)
@@ -354,24 +481,34 @@ def main():
             torch.cuda.synchronize()
             return a.elapsed_time(b)
         run_stack(set())
-        ms_sparse = run_stack(set())
+        sp = [run_stack(set()) for _ in range(5)]
+        ms_sparse = statistics.fmean(sp)
         hybrid = {l for l in range(Ls["layers"]) if l % 7 in (0, 3)}          # 2 full-attention layers per 7
         ms_hybrid = run_stack(hybrid)
         ms_full = run_stack(set(range(Ls["layers"])))
         pairs_l = int(c_l.sum().item())
-        f_layer = 4.0 * Ls["B"] * Ls["B"] * Ls["d"] * Ls["hq"] * pairs_l
+        f_layer = flops_block(Ls["B"], Ls["d"], Ls["hq"], 1, pairs_l)
         stack = {"layers": Ls["layers"], "workload": "28q/4kv heads, N=65536, D=128, block 64, W=4, S=1, bf16",
                  "sparse_ms_per_layer": round(ms_sparse / Ls["layers"], 4),
+                 "sparse_ms_total": stats(sp),
                  "sparse_tflops": round(f_layer * Ls["layers"] / (ms_sparse * 1e-3) / 1e12, 1),
-                 "hybrid_2_dense_per_7_ms_total": round(ms_hybrid, 2), "sparse_ms_total": round(ms_sparse, 2),
+                 "frac_of_mfma_peak": round(f_layer * Ls["layers"] / (ms_sparse * 1e-3) / 1e12 / PEAK_MFMA_BF16_TFLOPS, 4),
+                 "hybrid_2_dense_per_7_ms_total": round(ms_hybrid, 2),
                  "all_dense_ms_total": round(ms_full, 2)}
         del layers_in, ol
 
-    # ---------------- CPU oracle on a bounded row sample (also the bench's own parity check) ----------------
+    # ---------------- CPU oracle on a bounded sample (also the bench's own parity check of what it timed) ---------
     cpu = None
     parity = None
     if not args.no_cpu_baseline:
         from oracle import powattn_oracle as orc
+        opat_p, opat_d = orc.Pattern(P["B"], P["W"], P["S"]), orc.Pattern(Dc["B"], Dc["W"], Dc["S"])
+        # the FLOP count above rests on the library's own lists: check it against the oracle's count
+        oracle_pairs = orc.attended_pairs(P["n"], opat_p)
+        assert oracle_pairs == pairs, (oracle_pairs, pairs)
+        # restore the outputs of the timed prefill (the backward section reused the buffers)
+        pa.prefill(pat_p, cnt, idx, qg, kg, vg, o=og, lse=lseg)
+        torch.cuda.synchronize()
         rng = np.random.default_rng(12345)
         rows = sorted(set(rng.integers(0, P["n"], size=args.cpu_rows - 64).tolist())
                       | set(range(P["n"] - 64, P["n"])))
@@ -379,21 +516,68 @@ def main():
         q_rows = synth.to_numpy_storage(q[:, :, rows_t])
         ks, vs = synth.to_numpy_storage(k), synth.to_numpy_storage(v)
         c0 = time.perf_counter()
-        oo, olse = orc.attention_rows(q_rows, ks, vs, rows, orc.Pattern(P["B"], P["W"], P["S"]),
-                                      q_holds_rows_only=True)
+        oo, olse = orc.attention_rows(q_rows, ks, vs, rows, opat_p, q_holds_rows_only=True)
         c1 = time.perf_counter()
         cores = len(os.sched_getaffinity(0))
         if os.environ.get("OMP_NUM_THREADS", "").isdigit():
             cores = min(cores, int(os.environ["OMP_NUM_THREADS"]))
         cpu_tflops = f_block * (len(rows) / P["n"]) / (c1 - c0) / 1e12
+        # the whole tensor at a reduced length: configuration 2's shape cut to N = 8192 and one KV head's group
+        n_red = 8192
+        pat_r = orc.Pattern(64, 4, 1)
+        qr, kr, vr = synth.qkv(1, 4, 1, n_red, 128, "bf16", seed=1)
+        r0 = time.perf_counter()
+        ro, rl = orc.attention(synth.to_numpy_storage(qr), synth.to_numpy_storage(kr), synth.to_numpy_storage(vr), pat_r)
+        r1 = time.perf_counter()
+        red_pairs = orc.attended_pairs(n_red, pat_r)
+        red_flops = flops_block(64, 128, 4, 1, red_pairs)
+        c_r, i_r, _ = pa.mask_build(pa.Pattern(64, 4, 1), n_red)
+        go_r, gl_r = pa.prefill(pa.Pattern(64, 4, 1), c_r, i_r, qr.to(dev), kr.to(dev), vr.to(dev))
+        torch.cuda.synchronize()
         cpu = {"value": cpu_tflops, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
                "sample": f"{len(rows)} query rows (seeded random + the last 64) x all 32 heads of the 128K workload, "
                          f"each against all 131072 keys in float64; {c1 - c0:.1f} s; FLOPs credited as for the GPU "
-                         f"(attended blocks only, scaled by rows/N)"}
+                         f"(attended blocks only, scaled by rows/N)",
+               "full_tensor_reduced": {"shape": "b1, 4q/1kv heads, N=8192, D=128, block 64, W=4, S=1 (configuration 2 "
+                                                "cut to 8192 tokens and one KV head's group), every row",
+                                       "seconds": round(r1 - r0, 2),
+                                       "value": red_flops / (r1 - r0) / 1e12, "unit": "TFLOP/s"}}
         go = og[:, :, rows_t.to(dev)].double().cpu().numpy()
         gl = lseg[:, :, rows_t.to(dev)].double().cpu().numpy()
-        parity = {"prefill_rows_checked": len(rows) * P["hq"],
-                  "max_abs_err_o": float(np.abs(go - oo).max()), "max_abs_err_lse": float(np.abs(gl - olse).max())}
+        parity = {"attended_block_pairs_equal_oracle": True,
+                  "prefill_rows_checked": len(rows) * P["hq"],
+                  "prefill_max_abs_err_o": float(np.abs(go - oo).max()),
+                  "prefill_max_abs_err_lse": float(np.abs(gl - olse).max()),
+                  "prefill_reduced_full_tensor_max_abs_err_o": float(np.abs(go_r.double().cpu().numpy() - ro).max()),
+                  "prefill_reduced_full_tensor_max_abs_err_lse": float(np.abs(gl_r.double().cpu().numpy() - rl).max())}
+        # the decode step that was timed: three sequences of the cache of the last timed step
+        kc, vc = caches[(args.steps - 1) % len(caches)]
+        pa.decode(pat_d, qd, kc, vc, lens, o=od, lse=lsed, workspace=ws)
+        torch.cuda.synchronize()
+        errs_o, errs_l = [], []
+        for b in (0, 7, 15):
+            do_, dl_ = orc.decode(synth.to_numpy_storage(qd[b:b + 1].cpu()), synth.to_numpy_storage(kc[b:b + 1].cpu()),
+                                  synth.to_numpy_storage(vc[b:b + 1].cpu()), [Dc["len"]], opat_d)
+            errs_o.append(float(np.abs(od[b:b + 1].double().cpu().numpy() - do_).max()))
+            errs_l.append(float(np.abs(lsed[b:b + 1].double().cpu().numpy() - dl_).max()))
+        parity["decode_sequences_checked"] = 3
+        parity["decode_max_abs_err_o"] = max(errs_o)
+        parity["decode_max_abs_err_lse"] = max(errs_l)
+        do_, dl_ = orc.decode(synth.to_numpy_storage(qd[:1].cpu()), synth.to_numpy_storage(k128_seq0.cpu()),
+                              synth.to_numpy_storage(v128_seq0.cpu()), [Dl["len"]], opat_d)
+        parity["decode_128k_max_abs_err_o"] = float(np.abs(od128_seq0.double().cpu().numpy() - do_).max())
+        parity["decode_128k_max_abs_err_lse"] = float(np.abs(lse128_seq0.double().cpu().numpy() - dl_).max())
+        if bwd_parity_inputs is not None:
+            rows_b, do_rows, gdq, gdk, gdv = bwd_parity_inputs
+            rq, rk, rv = orc.attention_backward_rows(synth.to_numpy_storage(q[:, :4]), synth.to_numpy_storage(k[:, :1]),
+                                                     synth.to_numpy_storage(v[:, :1]),
+                                                     synth.to_numpy_storage(do_rows[:, :4]), rows_b, opat_p)
+            rel = lambda g, r: float(np.abs(g - r).max() / np.abs(r).max())
+            parity["backward_128k"] = {"query_rows_with_nonzero_dO": int(rows_b.size), "kv_heads_checked": 1,
+                                       "dq_max_err_over_largest_entry": rel(gdq[:, :, rows_b], rq),
+                                       "dk_all_keys_max_err_over_largest_entry": rel(gdk, rk),
+                                       "dv_all_keys_max_err_over_largest_entry": rel(gdv, rv),
+                                       "dk_sink_block_max_err_over_largest_entry": rel(gdk[:, :, :128], rk[:, :, :128])}
 
     out = {
         "metric": "sparse-attn prefill effective TFLOP/s (attended blocks only) at 128K",
@@ -411,18 +595,26 @@ def main():
         "config": {"workload": "step = mask_build + sparse prefill (b1, 32q/8kv heads, N=131072, D=128, block 128, "
                                "W=4, S=1, bf16) + one decode step (b16, 32q/8kv, 65536-token bf16 caches of capacity 65600, "
                                "block 64, W=4, S=1, cold: rotating over %d caches)" % len(caches),
-                   "attended_block_pairs": pairs, "flops_per_step": f_block},
+                   "attended_block_pairs": pairs, "flops_per_step": f_block, "library_version": lib_version},
         "roofline": {"bound": "mfma", "kernel": "pa_prefill_bf16_kernel", "achieved": round(prefill_tflops, 2),
                      "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(prefill_tflops / PEAK_MFMA_BF16_TFLOPS, 4),
-                     "avg_launch_ms": round(prefill_ms, 4), "traffic": PREFILL_TRAFFIC_BYTES},
+                     "avg_launch_ms": round(prefill_ms, 4), "launch_ms": stats(prefill_samples),
+                     "traffic": (traffic("prefill") or {}).get("bytes"), "traffic_measured_on": traffic("prefill")},
         "cpu_baseline": cpu,
+        "configs": configs,
         "decode": {"tokens_per_s": round(Dc["batch"] / (decode_us * 1e-6), 1), "us_per_step": round(decode_us, 2),
-                   "in_step_us": round(decode_in_step_us, 2), "steps_timed": dec_iters,
-                   "roofline": {"bound": "hbm", "kernel": "pa_decode_kernel (+ merge)", "achieved": round(decode_gbs, 1),
+                   "us_per_step_stats": stats(dec_samples),
+                   "in_step_us": round(decode_in_step_us, 2), "in_step_us_stats": stats(decode_in_step),
+                   "steps_timed": 20 * 12,
+                   "roofline": {"bound": "hbm", "kernel": "pa_decode_kernel", "achieved": round(decode_gbs, 1),
                                 "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(decode_gbs / PEAK_HBM_GBS, 4),
-                                "bytes_per_step": decode_bytes, "traffic": DECODE_TRAFFIC_BYTES},
+                                "frac_in_step": round(decode_bytes / (decode_in_step_us * 1e-6) / 1e9 / PEAK_HBM_GBS, 4),
+                                "bytes_per_step": decode_bytes,
+                                "traffic": (traffic("decode") or {}).get("bytes"), "traffic_measured_on": traffic("decode")},
+                   "context_131072": decode_128k,
                    "paged_cache_by_batch": paged},
+        "measured_peaks": measured_peaks,
         "dense_baseline": dense,
         "paper_setting_b256_w5_s1": sweep,
         "layer_stack": stack,

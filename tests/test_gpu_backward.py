@@ -1,7 +1,19 @@
 """GPU parity: powattn_backward (dQ, dK, dV of Equation 1 under the block pattern) vs the oracle's float64
-gradients on the same bf16 inputs.  Bar: max abs error 1e-2 relative to max(1, largest gradient entry) per
-tensor: the bf16 rounding of the stored gradient alone is 2^-9 = 0.2 % of an entry, and the probabilities and score
-gradients enter the second products rounded to bf16 as well (fp32 accumulation throughout)."""
+gradients on the same bf16 inputs.
+
+Bars, per gradient tensor (the benchmark spec gives none for gradients; derived from the kernel's arithmetic):
+  * max |got - ref| <= 8e-3 * max |ref|.  A stored gradient is bf16: rounding to nearest costs up to 2^-9 = 1.95e-3
+    of the entry itself.  P and dS enter the second products (dV = P^T dO, dQ = dS K, dK = dS^T Q) rounded to bf16
+    too: every term of those sums carries an independent relative error of up to 2^-9, i.e. a standard deviation of
+    about 2^-9 / sqrt(3) = 1.1e-3 of the root-sum-square of the terms, which for the large entries is of the order
+    of the entry; over the 1e5..1e7 entries of a tensor the worst of them sits 4-5 standard deviations out.  fp32
+    accumulation and the fp32 log-sum-exp / Delta are far below that.  2e-3 + 5.5e-3, rounded up: 8e-3 of the
+    largest entry.
+  * ||got - ref||_2 / ||ref||_2 <= 4e-3: the same three roundings as root-mean-square figures (about 1.1e-3 each for
+    uniform rounding errors, those inside the sums enlarged by cancellation between terms); unlike the max-norm
+    bar this one is sensitive to errors in the many small entries.
+Measured over the ~60 cases of this file and of the random shapes: max-norm 2.1e-3..6.5e-3 of the largest entry,
+relative root-mean-square 1.8e-3..3.0e-3."""
 import numpy as np
 import pytest
 import torch
@@ -12,7 +24,24 @@ from paper_2503_03588_amd import synth
 from gpu_util import oracle_pattern
 
 pytestmark = pytest.mark.gpu
-TOL_G = 1e-2
+TOL_G_MAX = 8e-3     # of the largest entry of the tensor
+TOL_G_RMS = 4e-3     # relative root-mean-square error of the tensor
+
+
+TOL_G_ABS = 1e-5     # absolute floor: where a gradient vanishes (a single token: P = 1, dS = dP - Delta = 0) the fp32
+                     # difference dP - Delta leaves ~2^-23 * |dO . v| ~ 1e-6, times scale * |k|
+
+
+def check_grad(name, got, ref):
+    """got, ref: float64 arrays of one gradient tensor (or a sample of it)."""
+    assert np.isfinite(got).all(), name
+    big = np.abs(ref).max()
+    err = np.abs(got - ref).max()
+    rms_err, rms_ref = float(np.sqrt(((got - ref) ** 2).mean())), float(np.sqrt((ref ** 2).mean()))
+    print(f"  {name}: max abs err {err:.3e} = {err / max(big, 1e-30):.2e} of the largest entry {big:.3f}; "
+          f"rms err {rms_err:.3e} = {rms_err / max(rms_ref, 1e-30):.2e} of the rms entry", flush=True)
+    assert err <= TOL_G_MAX * big + TOL_G_ABS, (name, err, big)
+    assert rms_err <= TOL_G_RMS * rms_ref + TOL_G_ABS, (name, rms_err, rms_ref)
 
 
 def run_backward(pat, batch, hq, hkv, n, d, seed, scale=0.0):
@@ -31,12 +60,7 @@ def run_backward(pat, batch, hq, hkv, n, d, seed, scale=0.0):
                                         synth.to_numpy_storage(v), synth.to_numpy_storage(do),
                                         oracle_pattern(pat), None if scale <= 0 else scale)
     for name, got, ref in (("dq", dq, rq), ("dk", dk, rk), ("dv", dv, rv)):
-        g = got.double().cpu().numpy()
-        assert np.isfinite(g).all(), name
-        err = np.abs(g - ref).max()
-        bar = TOL_G * max(1.0, np.abs(ref).max())
-        print(f"  {name}: max abs err {err:.3e} (largest entry {np.abs(ref).max():.3f}, bar {bar:.3e})", flush=True)
-        assert err <= bar, (name, err, bar)
+        check_grad(name, got.double().cpu().numpy(), ref)
 
 
 @pytest.mark.parametrize("B,W,S,flags,hq,hkv,n,d", [
@@ -73,7 +97,7 @@ def test_rows_outside_the_sink_blocks_are_reproducible():
     torch.cuda.synchronize()
     assert torch.equal(a[0], b[0])
     assert torch.equal(a[1][:, :, 64:], b[1][:, :, 64:]) and torch.equal(a[2][:, :, 64:], b[2][:, :, 64:])
-    assert (a[1][:, :, :64].float() - b[1][:, :, :64].float()).abs().max().item() <= 1e-2
+    assert (a[1][:, :, :64].float() - b[1][:, :, :64].float()).abs().max().item() <= 1e-2      # last bits only
 
 
 
@@ -103,9 +127,51 @@ def test_prefill_configuration_size_on_sampled_rows_and_keys():
         got = (dq[:, hs][:, :, rows].double().cpu().numpy(), dk[:, kvh:kvh + 1][:, :, keys].double().cpu().numpy(),
                dv[:, kvh:kvh + 1][:, :, keys].double().cpu().numpy())
         for name, g, ref in zip(("dq", "dk", "dv"), got, (rq, rk, rv)):
-            err, bar = np.abs(g - ref).max(), TOL_G * max(1.0, np.abs(ref).max())
-            print(f"  kv head {kvh} {name}: max abs err {err:.3e} (largest entry {np.abs(ref).max():.3f})", flush=True)
-            assert err <= bar, (kvh, name, err, bar)
+            check_grad(f"kv head {kvh} {name}", g, ref)
+
+
+def test_long_prefill_configuration_size_with_a_row_sparse_upstream_gradient():
+    # configuration 3 at its full size (batch 1, 32/8 heads, N = 131072, block 128, W = 4, S = 1): what the bench
+    # times as `backward_128k`, i.e. the split-wavefront dK/dV kernel with the sink block's column cut into 64 parts
+    # that add up in fp32.  The dense oracle is out of reach and so is the sampled one for sink keys (every query
+    # attends them).  Instead dO is zero outside 200 query rows that are spread over all 64 parts: then only those rows
+    # contribute to dK and dV (a row with dO = 0 has dS = 0), and the oracle's row-sparse form gives dK and dV of
+    # EVERY key: the sink block's rows, the diagonal and window blocks of the sampled rows and their power-of-two
+    # blocks, and exact zeros everywhere else; dQ is checked on the sampled rows and must be zero on the others.
+    pat = pa.Pattern(128, 4, 1)
+    hq, hkv, n, d = 32, 8, 131072, 128
+    print("backward at N=131072 B=128 32/8 heads, row-sparse dO", flush=True)
+    q, k, v = synth.qkv(1, hq, hkv, n, d, "bf16", seed=2)
+    rng = np.random.default_rng(64)
+    rows = np.unique(np.concatenate([[0, 127, 128, n - 1], 2048 * np.arange(64) + rng.integers(0, 2048, 64),
+                                     rng.integers(0, n, 140)]))
+    do_rows = synth.gaussian((1, hq, rows.size, d), "bf16", 65)
+    do = torch.zeros((1, hq, n, d), dtype=torch.bfloat16)
+    do[:, :, torch.from_numpy(rows)] = do_rows
+    cnt, idx, _ = pa.mask_build(pat, n)
+    qd, kd, vd, dod = q.cuda(), k.cuda(), v.cuda(), do.cuda()
+    o, lse = pa.prefill(pat, cnt, idx, qd, kd, vd)
+    dq, dk, dv = pa.backward(pat, cnt, idx, qd, kd, vd, o, lse, dod)
+    torch.cuda.synchronize()
+    opat = oracle_pattern(pat)
+    others = np.setdiff1d(np.arange(n), rows)
+    for kvh in (0, 7):
+        hs = slice(4 * kvh, 4 * kvh + 4)
+        rq, rk, rv = orc.attention_backward_rows(synth.to_numpy_storage(q[:, hs]), synth.to_numpy_storage(k[:, kvh:kvh + 1]),
+                                                 synth.to_numpy_storage(v[:, kvh:kvh + 1]),
+                                                 synth.to_numpy_storage(do_rows[:, hs]), rows, opat)
+        gq = dq[:, hs].double().cpu().numpy()
+        gk, gv = dk[:, kvh:kvh + 1].double().cpu().numpy(), dv[:, kvh:kvh + 1].double().cpu().numpy()
+        check_grad(f"kv head {kvh} dq (sampled rows)", gq[:, :, rows], rq)
+        assert (gq[:, :, others] == 0).all()
+        check_grad(f"kv head {kvh} dk (all keys)", gk, rk)
+        check_grad(f"kv head {kvh} dv (all keys)", gv, rv)
+        check_grad(f"kv head {kvh} dk (sink block)", gk[:, :, :128], rk[:, :, :128])
+        check_grad(f"kv head {kvh} dv (sink block)", gv[:, :, :128], rv[:, :, :128])
+        # keys that no sampled row attends get exactly nothing
+        untouched = (rk == 0).all(axis=-1) & (rv == 0).all(axis=-1)
+        assert untouched.sum() > 1000
+        assert (gk[untouched] == 0).all() and (gv[untouched] == 0).all()
 
 
 @pytest.mark.parametrize("B,W,S,flags,hq,hkv,n,d", [
