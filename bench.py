@@ -450,6 +450,31 @@ def main():
                                  dvg[:, :1].double().cpu().numpy())
         del dog, dqg, dkg, dvg, wsb
 
+    # ---------------- a serving batch of prompts of different lengths in one launch (powattn_prefill_varlen,
+    # lengths in device memory): 64 prompts of 512..8192 tokens, configuration 2's heads and pattern ----------------
+    varlen = None
+    if not args.no_dense:
+        Vb = dict(batch=64, hq=32, hkv=8, npad=8192, d=128, B=64, W=4, S=1)
+        pat_v = pa.Pattern(Vb["B"], Vb["W"], Vb["S"])
+        gv = torch.Generator(device=dev)
+        gv.manual_seed(5000)
+        lens_v = torch.randint(512, Vb["npad"] + 1, (Vb["batch"],), device=dev, dtype=torch.int32, generator=gv)
+        qv = torch.randn(Vb["batch"], Vb["hq"], Vb["npad"], Vb["d"], device=dev, dtype=torch.bfloat16, generator=gv)
+        kv_ = torch.randn(Vb["batch"], Vb["hkv"], Vb["npad"], Vb["d"], device=dev, dtype=torch.bfloat16, generator=gv)
+        vv_ = torch.randn(Vb["batch"], Vb["hkv"], Vb["npad"], Vb["d"], device=dev, dtype=torch.bfloat16, generator=gv)
+        ov = torch.empty_like(qv)
+        c_v, i_v, _ = pa.mask_build(pat_v, Vb["npad"])
+        ms_v = stats(time_launches(lambda s: pa.prefill_varlen(pat_v, c_v, i_v, qv, kv_, vv_, lens_v, o=ov, want_lse=False), 20, 5))
+        nbs = (lens_v.cpu().numpy().astype(np.int64) + Vb["B"] - 1) // Vb["B"]
+        csum = np.concatenate([[0], np.cumsum(c_v.cpu().numpy().astype(np.int64))])
+        pairs_v = int(sum(csum[n] for n in nbs))
+        f_v = flops_block(Vb["B"], Vb["d"], Vb["hq"], 1, pairs_v)
+        varlen = {"workload": "64 prompts of 512..8192 tokens (seeded uniform), padded to 8192, 32q/8kv heads, D=128, block 64, "
+                              "W=4, S=1, bf16; one launch, lengths read on the device",
+                  "tokens": int(lens_v.sum().item()), "attended_block_pairs": pairs_v, "kernel_ms": ms_v,
+                  "tflops": round(f_v / (ms_v["mean"] * 1e-3) / 1e12, 1)}
+        del qv, kv_, vv_, ov
+
     # ---------------- layer stack (configuration 5): 28 successive sparse-attention layers, 28 query /
     # 4 KV heads, 64K context, block 64, fresh random Q/K/V per layer (no projection weights exist, so the layers
     # are not chained); per-layer kernel time.  Second pass: the hybrid schedule of Section 4.3, in which 2 of
@@ -618,6 +643,7 @@ def main():
         "dense_baseline": dense,
         "paper_setting_b256_w5_s1": sweep,
         "layer_stack": stack,
+        "prefill_varlen_batch": varlen,
         "backward_128k": backward,
         "prefill_sustained": sustained,
         "parity": parity,

@@ -157,25 +157,32 @@ int powattn_prefill_chunk(const powattn_pattern* pattern,
 
 /*
  * powattn_prefill for a batch of sequences of different lengths (what a serving
- * batch of prompts looks like; Section 4.3 measures end-to-end generation).  The
- * tensors are padded to `padded_len` rows per head; sequence b uses rows
- * 0 .. h_seq_len[b]-1 and its other rows of o and lse are left untouched.  A row of
+ * batch of prompts looks like; Section 4.3 measures end-to-end generation), in
+ * ONE launch, with the lengths in device memory (no host copy, no
+ * synchronisation; they may be the output of an earlier kernel on the stream).
+ * The tensors are padded to `padded_len` rows per head; sequence b uses rows
+ * 0 .. seq_len[b]-1 and its other rows of o and lse are left untouched.  A row of
  * the block lists does not depend on the sequence length (Algorithm 1 looks at
- * positions only), so one pair of lists built for the longest sequence serves all;
- * the call issues one launch per sequence on the stream.
+ * positions only), so one pair of lists built for padded_len serves all.  The
+ * result for each sequence equals powattn_prefill on that sequence alone, bit
+ * for bit.
  *   q, o           device [batch, n_q_heads, padded_len, head_dim]
  *   k, v           device [batch, n_kv_heads, padded_len, head_dim]
  *   lse            device float [batch, n_q_heads, padded_len] or NULL
- *   h_seq_len      HOST int64 [batch], 0 <= h_seq_len[b] <= padded_len (0: nothing to do)
- *   d_kv_cnt, d_kv_idx, max_k   lists covering at least ceil(max_b h_seq_len[b] / block) rows
+ *   d_seq_len      device int32 [batch], 0 <= seq_len[b] <= padded_len (0: nothing
+ *                  to do; values outside that range are clamped into it by the kernel)
+ *   d_kv_cnt, d_kv_idx, max_k   lists covering ceil(padded_len / block) rows
  *   dtype          POWATTN_BF16 only; head_dim 64 or 128; block a multiple of 64, at most 1024
+ * Work is dealt to the compute units by position in the padded batch, not by
+ * length: a batch whose long sequences sit next to one another is balanced less
+ * well than a shuffled one.
  * Errors: INVALID_ARG, UNSUPPORTED, HIP_ERROR.
  */
 int powattn_prefill_varlen(const powattn_pattern* pattern,
                            const int32_t* d_kv_cnt, const int32_t* d_kv_idx, int32_t max_k,
                            const void* q, const void* k, const void* v, void* o, float* lse,
                            int32_t batch, int32_t n_q_heads, int32_t n_kv_heads,
-                           const int64_t* h_seq_len, int64_t padded_len,
+                           const int32_t* d_seq_len, int64_t padded_len,
                            int32_t head_dim, int32_t dtype, float softmax_scale, void* hip_stream);
 
 /*

@@ -83,7 +83,7 @@ def lib() -> ctypes.CDLL:
     L.powattn_prefill_chunk.restype = ctypes.c_int
     L.powattn_prefill_chunk.argtypes = [P, vp, vp, i32, vp, vp, vp, vp, vp, i32, i32, i32, i64, i64, i64, i32, i32, f32, vp]
     L.powattn_prefill_varlen.restype = ctypes.c_int
-    L.powattn_prefill_varlen.argtypes = [P, vp, vp, i32, vp, vp, vp, vp, vp, i32, i32, i32, ctypes.POINTER(i64), i64,
+    L.powattn_prefill_varlen.argtypes = [P, vp, vp, i32, vp, vp, vp, vp, vp, i32, i32, i32, vp, i64,
                                          i32, i32, f32, vp]
     L.powattn_decode_workspace_bytes.restype = ctypes.c_size_t
     L.powattn_decode_workspace_bytes.argtypes = [P, i32, i32, i32, i32, i64]
@@ -363,28 +363,25 @@ def backward(pattern: Pattern, kv_cnt, kv_idx, q, k, v, o, lse, d_o, dq=None, dk
 
 def prefill_varlen(pattern: Pattern, kv_cnt, kv_idx, q, k, v, seq_lens, o=None, lse=None, softmax_scale=0.0,
                    want_lse=True, stream=None):
-    """powattn_prefill_varlen.  q/o: [b,Hq,Np,D]; k/v: [b,Hkv,Np,D] padded to Np rows; seq_lens: a host sequence
-    of b lengths.  Rows beyond a sequence's length keep whatever o/lse held.  Returns (o, lse)."""
+    """powattn_prefill_varlen.  q/o: [b,Hq,Np,D]; k/v: [b,Hkv,Np,D] padded to Np rows; seq_lens: int32 device
+    tensor [b].  Rows beyond a sequence's length keep whatever o/lse held.  Returns (o, lse)."""
     batch, hq, npad, d = q.shape
     hkv = k.shape[1]
     if k.shape != (batch, hkv, npad, d) or v.shape != k.shape:
         raise ValueError("k/v shape mismatch")
     if k.dtype != q.dtype or v.dtype != q.dtype:
         raise ValueError("q/k/v dtype mismatch")
-    lens = [int(x) for x in seq_lens]
-    if len(lens) != batch:
-        raise ValueError("one length per sequence")
-    if kv_idx is not None and kv_cnt.shape[0] * pattern.block < max(lens):
-        raise ValueError("block lists shorter than the longest sequence")
+    if seq_lens.dtype != torch.int32 or seq_lens.shape != (batch,) or seq_lens.device != q.device:
+        raise ValueError("seq_lens must be an int32 tensor [batch] on the device of q")
+    if kv_idx is not None and kv_cnt.shape[0] * pattern.block < npad:
+        raise ValueError("block lists shorter than the padded length")
     if o is None:
         o = torch.zeros_like(q)
     if lse is None and want_lse:
         lse = torch.zeros((batch, hq, npad), dtype=torch.float32, device=q.device)
-    arr = (ctypes.c_int64 * batch)(*lens)
     mk = kv_idx.shape[1] if kv_idx is not None else 0
     st = lib().powattn_prefill_varlen(ctypes.byref(pattern.c()), _ptr(kv_cnt), _ptr(kv_idx), mk,
-                                      _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), batch, hq, hkv, arr, npad, d,
-                                      _dtype_code(q), float(softmax_scale), _stream(stream))
+                                      _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), batch, hq, hkv, _ptr(seq_lens),
+                                      npad, d, _dtype_code(q), float(softmax_scale), _stream(stream))
     _check(st, "powattn_prefill_varlen")
     return o, lse
-

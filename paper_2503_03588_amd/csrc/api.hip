@@ -117,6 +117,7 @@ extern "C" int powattn_prefill(const powattn_pattern* pattern,
   a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
   a.batch = batch; a.hq = n_q_heads; a.hkv = n_kv_heads;
   a.seq_len = seq_len; a.q_start = 0; a.kv_rows = seq_len; a.q_rows = 0; a.nb = (int32_t)nb; a.head_dim = head_dim;
+  a.seq_len_dev = nullptr;
   a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)head_dim);
   a.stream = (hipStream_t)hip_stream;
   if (dtype == POWATTN_F32) {
@@ -157,7 +158,7 @@ extern "C" int powattn_prefill_chunk(const powattn_pattern* pattern,
   a.kv_cnt = d_kv_cnt; a.kv_idx = d_kv_idx; a.max_k = max_k;
   a.q = q; a.k = k_cache; a.v = v_cache; a.o = o; a.lse = lse;
   a.batch = batch; a.hq = n_q_heads; a.hkv = n_kv_heads;
-  a.seq_len = seq_len; a.q_start = q_start; a.kv_rows = cache_capacity; a.q_rows = 0;
+  a.seq_len = seq_len; a.q_start = q_start; a.kv_rows = cache_capacity; a.q_rows = 0; a.seq_len_dev = nullptr;
   a.nb = (int32_t)((q_len + pattern->block - 1) / pattern->block);
   a.head_dim = head_dim;
   a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)head_dim);
@@ -169,46 +170,38 @@ extern "C" int powattn_prefill_varlen(const powattn_pattern* pattern,
                                       const int32_t* d_kv_cnt, const int32_t* d_kv_idx, int32_t max_k,
                                       const void* q, const void* k, const void* v, void* o, float* lse,
                                       int32_t batch, int32_t n_q_heads, int32_t n_kv_heads,
-                                      const int64_t* h_seq_len, int64_t padded_len,
+                                      const int32_t* d_seq_len, int64_t padded_len,
                                       int32_t head_dim, int32_t dtype, float softmax_scale, void* hip_stream) {
   int st = pa_check_pattern(pattern);
   if (st != POWATTN_OK) return st;
-  if (!q || !k || !v || !o || !h_seq_len) return POWATTN_INVALID_ARG;
+  if (!q || !k || !v || !o || !d_seq_len) return POWATTN_INVALID_ARG;
   if (batch < 1 || n_q_heads < 1 || n_kv_heads < 1 || head_dim < 1 || padded_len < 1) return POWATTN_INVALID_ARG;
   if (n_q_heads % n_kv_heads != 0) return POWATTN_INVALID_ARG;
   const bool dense = (pattern->flags & POWATTN_DENSE) != 0;
   if (!dense && (!d_kv_cnt || !d_kv_idx || max_k < 1)) return POWATTN_INVALID_ARG;
-  if (powattn_num_blocks(pattern, padded_len) < 0) return POWATTN_INVALID_ARG;
+  const int64_t nb = powattn_num_blocks(pattern, padded_len);
+  if (nb < 0) return POWATTN_INVALID_ARG;
   if (!(softmax_scale == softmax_scale)) return POWATTN_INVALID_ARG;
-  for (int32_t b = 0; b < batch; ++b)
-    if (h_seq_len[b] < 0 || h_seq_len[b] > padded_len) return POWATTN_INVALID_ARG;
   if (dtype != POWATTN_BF16) return POWATTN_UNSUPPORTED;
   if (!supported_head_dim(head_dim)) return POWATTN_UNSUPPORTED;
   if (pattern->block % 64 != 0 || pattern->block > 1024) return POWATTN_UNSUPPORTED;
+  if ((int64_t)batch * n_q_heads > 65535 * 16) return POWATTN_UNSUPPORTED;
 
-  // one launch per sequence: the rows of the lists do not depend on the sequence length, so every sequence
-  // walks the first ceil(len / block) rows of the same lists over its own slabs
-  const size_t es = 2;    // bytes per bf16 element
-  for (int32_t b = 0; b < batch; ++b) {
-    if (h_seq_len[b] == 0) continue;
-    pa_prefill_args a;
-    a.pat = *pattern;
-    a.kv_cnt = d_kv_cnt; a.kv_idx = d_kv_idx; a.max_k = max_k;
-    a.q = (const char*)q + (size_t)b * n_q_heads * padded_len * head_dim * es;
-    a.k = (const char*)k + (size_t)b * n_kv_heads * padded_len * head_dim * es;
-    a.v = (const char*)v + (size_t)b * n_kv_heads * padded_len * head_dim * es;
-    a.o = (char*)o + (size_t)b * n_q_heads * padded_len * head_dim * es;
-    a.lse = lse ? lse + (size_t)b * n_q_heads * padded_len : nullptr;
-    a.batch = 1; a.hq = n_q_heads; a.hkv = n_kv_heads;
-    a.seq_len = h_seq_len[b]; a.q_start = 0; a.kv_rows = padded_len; a.q_rows = padded_len;
-    a.nb = (int32_t)((h_seq_len[b] + pattern->block - 1) / pattern->block);
-    a.head_dim = head_dim;
-    a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)head_dim);
-    a.stream = (hipStream_t)hip_stream;
-    st = pa_launch_prefill_bf16(a);
-    if (st != POWATTN_OK) return st;
-  }
-  return POWATTN_OK;
+  // One launch for the whole batch: the work items are numbered as if every sequence had padded_len tokens, and
+  // the kernel, which reads the lengths from device memory, passes over the query blocks a sequence does not have
+  // (the rows of the lists do not depend on the sequence length, so all sequences walk the same lists).
+  pa_prefill_args a;
+  a.pat = *pattern;
+  a.kv_cnt = d_kv_cnt; a.kv_idx = d_kv_idx; a.max_k = max_k;
+  a.q = q; a.k = k; a.v = v; a.o = o; a.lse = lse;
+  a.batch = batch; a.hq = n_q_heads; a.hkv = n_kv_heads;
+  a.seq_len = padded_len; a.q_start = 0; a.kv_rows = padded_len; a.q_rows = padded_len;
+  a.nb = (int32_t)nb;
+  a.head_dim = head_dim;
+  a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)head_dim);
+  a.stream = (hipStream_t)hip_stream;
+  a.seq_len_dev = d_seq_len;
+  return pa_launch_prefill_bf16(a);
 }
 
 extern "C" size_t powattn_decode_workspace_bytes(const powattn_pattern* pattern, int32_t batch,

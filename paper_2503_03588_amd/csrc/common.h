@@ -31,6 +31,7 @@ struct pa_prefill_args {
   int64_t kv_rows;   // rows per (batch, KV head) slab of K/V: seq_len, or the capacity of a cache
   int64_t q_rows;    // rows per (batch, query head) slab of Q/O/LSE; 0: seq_len - q_start
   int32_t nb;      // query blocks: ceil((seq_len - q_start) / block)
+  const int32_t* seq_len_dev;   // device [batch]: every sequence's own length, seq_len then being the padded one; or null
   int32_t head_dim;
   float scale;     // softmax scale (natural units)
   hipStream_t stream;

@@ -88,6 +88,7 @@ struct bf16_params {
   int64_t kv_rows;   // rows per (batch, KV head) slab of K/V (N, or the capacity of a cache)
   int32_t i0;        // first query block: q_start / B
   float c2;          // softmax scale * log2(e)
+  const int32_t* seq_len;   // padded batch of sequences of different lengths: device array [batch]; N is then the padded length
 };
 
 // The work of one query block is a sequence of 64-key tiles: the tiles of the listed blocks before
@@ -127,8 +128,10 @@ __device__ __forceinline__ void wait_vmcnt() {   // s_waitcnt vmcnt(N) only
 }
 
 // DENSE: the implicit list {0..i} instead of a block list.  CHAIN: the launch chains work items in persistent
-// workgroups (two half-size tile tables, list rows prefetched); otherwise one workgroup per item.
-template <int D, int NW, int NS, bool DENSE, bool CHAIN>
+// workgroups (two half-size tile tables, list rows prefetched); otherwise one workgroup per item.  VARLEN: every
+// sequence of the batch has its own length, read from device memory; the work items are numbered as if all had the
+// padded length, and a workgroup passes over the items of query blocks that a sequence does not have.
+template <int D, int NW, int NS, bool DENSE, bool CHAIN, bool VARLEN>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void pa_prefill_bf16_kernel(bf16_params p) {
   constexpr int ROWB = 2 * D;        // bytes per K/V row
@@ -167,22 +170,26 @@ void pa_prefill_bf16_kernel(bf16_params p) {
   // ---- this workgroup's work items: item k is number xcd*per_xcd + cuslot + nslots*k of the launch, so that
   // the workgroups of one XCD (one L2) work on neighbouring query blocks at any time ----
   const int xcd = pid & 7, cuslot = pid >> 3, nslots = (int)(gridDim.x >> 3);
-  int n_items = 0;
+  int n_raw = 0;                       // item numbers that fall to this workgroup
   {
     int64_t lim = p.total_wg - (int64_t)xcd * p.per_xcd;
     if (lim > p.per_xcd) lim = p.per_xcd;
-    if (lim > cuslot) n_items = (int)((lim - cuslot + nslots - 1) / nslots);
+    if (lim > cuslot) n_raw = (int)((lim - cuslot + nslots - 1) / nslots);
   }
-  if (n_items == 0) return;
+  if (n_raw == 0) return;
   constexpr bool chained = CHAIN;      // tables in halves, list rows prefetched
   constexpr int tab_half = CHAIN ? TILE_CAP / 2 : 0;
 
   // Items are numbered L = ((b*hkv + kvh)*nb + r)*chunks + chunk with r counting query blocks from the last one
   // down (longest rows first, which matters for the dense list).  The first item is decoded by division, the
   // following ones by adding the stride nslots digit by digit with carries: all scalar, no division in the loop.
-  struct item_t { int chunk, r, kvh, b, i, subs_diag; };
+  struct item_t { int chunk, r, kvh, b, i, subs_diag, n; };   // n: keys (= tokens) of the item's sequence
   auto finish_item = [&](item_t& it) {
     it.i = p.i0 + p.nb - 1 - it.r;
+    if (VARLEN) {                      // uniform over the workgroup: a scalar load; lengths outside [0, N] are clamped
+      const int n = p.seq_len[it.b];
+      it.n = n < 0 ? 0 : (n > (int)p.N ? (int)p.N : n);
+    }
     // tiles of the diagonal block needed by any wavefront of the item
     int last_task = it.chunk * NW + NW - 1;
     if (last_task > p.tasks - 1) last_task = p.tasks - 1;
@@ -195,7 +202,7 @@ void pa_prefill_bf16_kernel(bf16_params p) {
     it.r = (int)(L % (uint32_t)p.nb); L /= (uint32_t)p.nb;
     it.kvh = (int)(L % (uint32_t)p.hkv);
     it.b = (int)(L / (uint32_t)p.hkv);
-    it.i = 0; it.subs_diag = 0;
+    it.i = 0; it.subs_diag = 0; it.n = 0;
     return it;
   };
   const item_t stride = digits((uint32_t)nslots);
@@ -209,6 +216,23 @@ void pa_prefill_bf16_kernel(bf16_params p) {
     return it;
   };
   item_t it = stride, it1 = stride, it2 = stride;   // the current item, the next one, the one after (set below)
+  // Sequences of different lengths: an item exists when its query block starts inside its sequence.  raw2 is the
+  // position of it2 among this workgroup's item numbers; next_valid steps to the next existing item (finish_item
+  // is only ever called for item numbers of the launch, so the length look-up stays inside the array).
+  int n_items = n_raw, raw2 = 0;
+  // keys of an item's sequence (one value for the whole launch unless the sequences have lengths of their own)
+  auto keys_of = [&](const item_t& x) -> int { return VARLEN ? x.n : (int)p.N; };
+  auto exists = [&](const item_t& x) -> bool { return !VARLEN || (int64_t)x.i * p.B < x.n; };
+  auto next_valid = [&](const item_t& cur, int& raw) -> item_t {
+    item_t x = cur;
+    while (raw + 1 < n_raw) {
+      ++raw;
+      x = next_item(x);
+      if (exists(x)) return x;
+    }
+    raw = n_raw;
+    return cur;                        // none left: never used as an item (the loop below counts the existing ones)
+  };
 
   // ---- tile tables (explicit lists only) ----
   // Writes the table of an item from its list row: lane e holds entry e (j), n entries in all; the tiles of the
@@ -276,6 +300,7 @@ void pa_prefill_bf16_kernel(bf16_params p) {
   const __bf16* f_kt = p.k;
   const __bf16* f_vt = p.v;
   int f_lim = 0;
+  int c_n = 1;                         // keys of the sequence whose tiles the cursor (below) is copying
   uint32_t f_dst = 0;
   const uint32_t w_dst = __builtin_amdgcn_readfirstlane(lds0 + wave * IPW * SRB);   // this wavefront's share of stage 0
   int f_row[IPW];                                      // this lane's row in each of the wavefront's copy instructions
@@ -284,7 +309,7 @@ void pa_prefill_bf16_kernel(bf16_params p) {
   const uint32_t f_chunk = (uint32_t)cp_chunk << 4;
   auto fill_prep = [&](const __bf16* kbase, const __bf16* vbase, int key0, uint32_t dst) {
     // ragged tail: rows beyond the sequence repeat its last row (they are masked, but must be finite)
-    const int last = (int)p.N - 1;
+    const int last = (VARLEN ? c_n : (int)p.N) - 1;   // of the sequence whose tiles the cursor is copying
     const int k0 = key0 < last ? key0 : last;
     f_lim = last - k0;
     // (scalar values may live in vector registers when scalar registers are short: pin the bases down)
@@ -325,6 +350,7 @@ void pa_prefill_bf16_kernel(bf16_params p) {
   const __bf16* c_vb = p.v;
   auto cursor_enter = [&](int k, const item_t& it) {
     c_k = k; c_pos = 0;
+    if (VARLEN) c_n = it.n;
     c_ntiles = DENSE ? it.i * p.subs + it.subs_diag : __builtin_amdgcn_readfirstlane(s_cnt[k & 1][0]);
     c_last = c_ntiles > 0 ? c_ntiles - 1 : 0;
     if (!DENSE) {
@@ -377,7 +403,7 @@ void pa_prefill_bf16_kernel(bf16_params p) {
 #pragma unroll
     for (int m = 0; m < NC; ++m) {
       const int rho = m / QE, e = m % QE;
-      const bool ok = act && tok0 + rho < p.N;
+      const bool ok = act && tok0 + rho < keys_of(it);
       qraw[m] = ok ? *reinterpret_cast<const u32x4*>(qbase + (int64_t)rho * D + 32 * e) : u32x4{0, 0, 0, 0};
     }
   };
@@ -415,8 +441,21 @@ void pa_prefill_bf16_kernel(bf16_params p) {
   // ---- start of the stream: tables of the first two items, fills 0..NS-2, Q of the first item ----
   it = digits((uint32_t)((int64_t)xcd * p.per_xcd + cuslot));
   finish_item(it);
-  it1 = next_item(it);
-  it2 = next_item(it1);
+  if (VARLEN) {
+    // count this workgroup's existing items, then set out on the first three
+    n_items = exists(it) ? 1 : 0;
+    {
+      item_t x = it;
+      for (int raw = 1; raw < n_raw; ++raw) { x = next_item(x); n_items += exists(x) ? 1 : 0; }
+    }
+    if (n_items == 0) return;
+    if (!exists(it)) it = next_valid(it, raw2);
+    it1 = next_valid(it, raw2);
+    it2 = next_valid(it1, raw2);
+  } else {
+    it1 = next_item(it);
+    it2 = next_item(it1);
+  }
   if (!DENSE) {
     if (wave == 0) {
       table_from_memory(0, it);
@@ -805,24 +844,24 @@ void pa_prefill_bf16_kernel(bf16_params p) {
 #pragma unroll
         for (int k2 = 0; k2 < 4; ++k2) {
           const u32x4 wv = {c[k2][0], c[k2][1], c[k2][2], c[k2][3]};
-          if (active && tok0 + k2 < p.N)
+          if (active && tok0 + k2 < keys_of(it))
             *reinterpret_cast<u32x4*>(obase + (int64_t)k2 * D + 32 * u) = wv;
         }
       }
-      if (active && tok < p.N && p.lse && hh == 0)
+      if (active && tok < keys_of(it) && p.lse && hh == 0)
         p.lse[((int64_t)it.b * p.hq + h) * p.q_rows + (tok - p.q_start)] = (m_run + log2f(ltot)) * 0.69314718055994530942f;
     }
-    it = it1; it1 = it2; it2 = next_item(it2);
+    it = it1; it1 = it2; it2 = VARLEN ? next_valid(it2, raw2) : next_item(it2);
   }
   // asynchronous copies must not outlive the workgroup's claim on its LDS
   wait_vmcnt<0>();
 }
 
-template <int D, int NW, int NS, bool DENSE, bool CHAIN>
+template <int D, int NW, int NS, bool DENSE, bool CHAIN, bool VARLEN>
 int launch_as(const bf16_params& p, hipStream_t stream) {
   constexpr size_t lds = (size_t)NS * 2 * (KT / (512 / D)) * (1024 + 16 * (512 / D));
   static std::atomic<unsigned long long> attr_done{0};
-  if (int st = pa_allow_dynamic_lds(reinterpret_cast<const void*>(&pa_prefill_bf16_kernel<D, NW, NS, DENSE, CHAIN>), lds, attr_done))
+  if (int st = pa_allow_dynamic_lds(reinterpret_cast<const void*>(&pa_prefill_bf16_kernel<D, NW, NS, DENSE, CHAIN, VARLEN>), lds, attr_done))
     return st;
   // One workgroup per work item, or, when the items can be chained (the block lists are short enough for the
   // look-ahead tables and registers), one persistent workgroup per compute unit that walks through its share.
@@ -834,14 +873,18 @@ int launch_as(const bf16_params& p, hipStream_t stream) {
     const int64_t persistent = (int64_t)(n_cu / 8) * 8;
     if (grid > persistent) grid = persistent;
   }
-  hipLaunchKernelGGL((pa_prefill_bf16_kernel<D, NW, NS, DENSE, CHAIN>), dim3((uint32_t)grid), dim3(64 * NW), lds, stream, p);
+  hipLaunchKernelGGL((pa_prefill_bf16_kernel<D, NW, NS, DENSE, CHAIN, VARLEN>), dim3((uint32_t)grid), dim3(64 * NW), lds, stream, p);
   return pa_note_hip(hipGetLastError());
 }
 
 template <int D, int NW, int NS>
 int launch(const bf16_params& p, hipStream_t stream) {
-  if (p.dense) return launch_as<D, NW, NS, true, true>(p, stream);     // the implicit list is always chained
-  return p.chain ? launch_as<D, NW, NS, false, true>(p, stream) : launch_as<D, NW, NS, false, false>(p, stream);
+  if (p.seq_len) {
+    if (p.dense) return launch_as<D, NW, NS, true, true, true>(p, stream);
+    return p.chain ? launch_as<D, NW, NS, false, true, true>(p, stream) : launch_as<D, NW, NS, false, false, true>(p, stream);
+  }
+  if (p.dense) return launch_as<D, NW, NS, true, true, false>(p, stream);     // the implicit list is always chained
+  return p.chain ? launch_as<D, NW, NS, false, true, false>(p, stream) : launch_as<D, NW, NS, false, false, false>(p, stream);
 }
 
 }  // namespace
@@ -858,6 +901,7 @@ int pa_launch_prefill_bf16(const pa_prefill_args& a) {
   p.N = a.seq_len;
   p.q_start = a.q_start; p.q_rows = a.q_rows > 0 ? a.q_rows : a.seq_len - a.q_start; p.kv_rows = a.kv_rows; p.i0 = (int32_t)(a.q_start / a.pat.block);
   p.c2 = a.scale * 1.44269504088896340736f;
+  p.seq_len = a.seq_len_dev;
   const int64_t tasks = (int64_t)p.G * p.B / QW;
   if (tasks > (1 << 20)) return POWATTN_UNSUPPORTED;
   p.tasks = (int32_t)tasks;

@@ -145,9 +145,9 @@ def test_prefill_chunk_argument_errors(L):
 
 def test_prefill_varlen_argument_errors(L):
     cp = pa.Pattern(64, 4, 1).c()
-    lens = (ctypes.c_int64 * 2)(1000, 2048)
 
-    def call(q=FAKE, lens_=lens, npad=2048, hq=4, hkv=2, d=128, dtype=pa.BF16, max_k=13, cnt=FAKE, pat=cp):
+    def call(q=FAKE, lens_=FAKE, npad=2048, hq=4, hkv=2, d=128, dtype=pa.BF16, max_k=13, cnt=FAKE, pat=cp):
+        # the lengths live in device memory: the host checks the pointer only (the kernel clamps the values)
         return L.powattn_prefill_varlen(ctypes.byref(pat), cnt, FAKE, max_k, q, FAKE, FAKE, FAKE, None, 2, hq, hkv,
                                         lens_, npad, d, dtype, 0.0, None)
     assert call(q=None) == pa.INVALID_ARG
@@ -155,8 +155,6 @@ def test_prefill_varlen_argument_errors(L):
     assert call(cnt=None) == pa.INVALID_ARG
     assert call(npad=0) == pa.INVALID_ARG
     assert call(hq=6, hkv=4) == pa.INVALID_ARG
-    assert call(npad=2000) == pa.INVALID_ARG                       # a sequence longer than the padding
-    assert call(lens_=(ctypes.c_int64 * 2)(-1, 5)) == pa.INVALID_ARG
     assert call(dtype=pa.F32) == pa.UNSUPPORTED
     assert call(d=96) == pa.UNSUPPORTED
     assert call(pat=pa.Pattern(48, 4, 1).c()) == pa.UNSUPPORTED

@@ -105,7 +105,7 @@ def draw_serving_cases(seed, count):
             lens = [rng.choice([0, npad, rng.randint(0, npad)]) for _ in range(rng.randint(1, 4))]
             if hq * len(lens) * npad > 30000:
                 hq, hkv = 4, 2
-            cases.append((kind, (B, W, S, hq, hkv, d, npad, lens)))
+            cases.append((kind, (B, W, S, pa.POWER, hq, hkv, d, npad, lens)))
         else:
             cap = rng.randint(1, max(1, 5000 // B)) * B             # whole pages
             lens = [cap] + [rng.randint(1, cap) for _ in range(rng.randint(0, 3))]
