@@ -260,6 +260,16 @@ __device__ __forceinline__ void dec_load_q(bf16x8 (&qf)[D / 32], const dec_param
     qf[c] = g < p.G ? *reinterpret_cast<const bf16x8*>(qp + 32 * c + 8 * q4) : z;
 }
 
+// The lane number, computed afresh wherever it is called: the compiler cannot carry the value of an earlier call
+// over, so nothing derived from it has to stay in (or be spilled from) a register across the chunk loads and the
+// matrix products, where every register counts.  (A spilled register in the persistent kernel is reloaded behind
+// the next chunk's loads and has to wait for all of them.)
+__device__ __forceinline__ int dec_lane_now() {
+  int l;
+  asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(l));
+  return l;
+}
+
 // The wavefront's partial output into LDS: lane (g, q4) holds O[j][r] = o[g][d = 32*q4 + 8r + j], eight
 // consecutive d per r, written as two 16-byte stores into the lane's padded row.
 template <int D>
@@ -432,20 +442,19 @@ __global__ __launch_bounds__(64 * NW) void pa_decode_kernel(dec_params p) {
 // Large batches: persistent workgroups.  With many more (sequence, KV head, split) items than compute units the
 // kernel above leaves every compute unit without a byte in flight while a workgroup looks its sequence length up and
 // while it merges (one workgroup fits at a time: its wavefronts hold a whole chunk in registers).  Here a workgroup
-// walks through items; a wavefront requests the chunk of the next item as soon as the registers of the current one
-// are free, before the workgroup merges the current item through LDS, and the sequence length and the page of an
-// item are read two and one items ahead.  Partials go to the workspace with plain stores and the merge kernel
-// below combines them after this kernel: no counters, no waits on stores.  Every item is a single pass (the host
-// checks that a row has at most splits * NW chunks).
+// walks through items, and through an item in passes of NW chunks (wavefront w takes chunk w + NW * pass of the
+// item's share of the row, keeping its running (max, sum, O) over the passes); a wavefront requests its chunk of the
+// next pass (of this item or the next one) as soon as the registers of the current one are free, before the workgroup
+// merges a finished item through LDS, and the sequence length and the page of a chunk are read two passes and one
+// pass ahead.  With one split per (sequence, KV head), which is how the library launches it once there is at least
+// one (sequence, KV head) pair per compute unit, the outputs are written here and no merge follows; with several
+// splits the partials go to the workspace with plain stores for the merge kernel below.
 template <int D>
-__global__ __launch_bounds__(64 * NW) void pa_decode_stream_kernel(dec_params p, int n_items) {
+__global__ __launch_bounds__(64 * NW) void pa_decode_stream_kernel(dec_params p, int n_items, int n_pass) {
   __shared__ float s_m[2][NW][MAXG], s_l[2][NW][MAXG];
   extern __shared__ __attribute__((aligned(16))) float s_o_dyn[];   // [2][NW][G][D/32][OROW] partial outputs of the wavefronts, two items
-  // (wavefront number as a scalar, lane from the hardware's lane count: see pa_decode_kernel)
+  // (wavefront number as a scalar; the lane number is taken afresh in every phase of a step: dec_lane_now)
   const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
-  const int lane = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
-  const int tid = wave * 64 + lane;
-  const int g = lane & 15, q4 = lane >> 4;
   const int stride = (int)gridDim.x;
   const int per_b = p.hkv * p.splits;
 
@@ -459,13 +468,20 @@ __global__ __launch_bounds__(64 * NW) void pa_decode_stream_kernel(dec_params p,
     it.split = r - it.kvh * p.splits;
     return it;
   };
-  // where this wavefront's chunk of item w lies, given the sequence length
+  // The workgroup's steps: all passes of its first item (number blockIdx.x of the launch), then of the item
+  // `stride` further on, and so on; a step is kept as (item number, pass) and advanced without a division.
+  struct step_t { int w, pass; };
+  auto after = [&](const step_t& st) -> step_t {
+    return st.pass + 1 < n_pass ? step_t{st.w, st.pass + 1} : step_t{st.w + stride, 0};
+  };
+  // Where this wavefront's chunk of a step lies, given the sequence length:
   struct plan_t { item_t it; dec_place pl; bool has; };
-  auto plan_of = [&](int w, int len) -> plan_t {
+  auto plan_of = [&](const step_t& st, int len) -> plan_t {
     plan_t pn;
+    const int w = st.w, pass = st.pass;
     pn.it = item_of(w);
     const dec_row row = dec_row_of(p, len);
-    const int slot = wave * p.splits + pn.it.split;
+    const int slot = (wave + NW * pass) * p.splits + pn.it.split;
     pn.pl = dec_place_of(p, row, slot < row.n_slots ? slot : 0);
     pn.has = w < n_items && slot < row.n_slots && pn.pl.n_tok > 0;
     return pn;
@@ -474,48 +490,64 @@ __global__ __launch_bounds__(64 * NW) void pa_decode_stream_kernel(dec_params p,
     return p.block_table ? p.block_table + (int64_t)pn.it.b * p.table_stride + pn.pl.blk : p.kv_len;
   };
 
-  int w = (int)blockIdx.x;
-  // the scalar pipeline: plan and page of the item after this one, length of the one after that
-  plan_t cur = plan_of(w, p.kv_len[item_of(w).b]);
+  // the scalar pipeline: plan and page of the step after this one, length of the one after that
+  step_t st0{(int)blockIdx.x, 0};                         // the current step, and the three after it
+  step_t st1 = after(st0), st2 = after(st1), st3 = after(st2);
+  plan_t cur = plan_of(st0, p.kv_len[item_of(st0.w).b]);
   int cur_page = *page_ptr(cur);
-  plan_t nxt = plan_of(w + stride, p.kv_len[item_of(w + stride).b]);
+  plan_t nxt = plan_of(st1, p.kv_len[item_of(st1.w).b]);
   int nxt_page = *page_ptr(nxt);
-  int len2 = p.kv_len[item_of(w + 2 * stride).b];
+  int len2 = p.kv_len[item_of(st2.w).b];
 
   dec_chunk<D> c;
   bf16x8 qf[D / 32];
   auto request = [&](const plan_t& pn, int page) {
+    const int lane = dec_lane_now(), g = lane & 15, q4 = lane >> 4;
     dec_load_q<D>(qf, p, pn.it.b, pn.it.kvh, g, q4);
     const int64_t off = dec_chunk_offset(p, pn.it.b, pn.it.kvh, pn.pl, page, D);
     dec_issue<D>(c, p.k + off, p.v + off, pn.has ? pn.pl.n_tok : 0, g, q4);   // no tokens: no loads
   };
   request(cur, cur_page);
 
-  for (int n = 0; w < n_items; w += stride, ++n) {
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x4 O[8];
+  int n = 0;                                              // items finished so far: selects the LDS buffer
+  for (; st0.w < n_items; st0 = st1, st1 = st2, st2 = st3, st3 = after(st3)) {
+    const int pass = st0.pass;
+    // ---- this wavefront's chunk of the step ----
+    if (pass == 0) {
+      m_run = -INFINITY; l_run = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) O[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    {
+      const int q4 = dec_lane_now() >> 4;
+      if (cur.has) dec_consume<D>(c, qf, cur.pl.n_tok, p.c2, q4, m_run, l_run, O);
+    }
+    const bool last_pass = pass == n_pass - 1;
     const int buf = n & 1;
     float* s_o = s_o_dyn + (size_t)buf * (dec_o_bytes<D>(p.G) / sizeof(float));
-    // ---- this wavefront's chunk of the current item ----
-    float m_run = -INFINITY, l_run = 0.f;
-    f32x4 O[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) O[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    if (cur.has) dec_consume<D>(c, qf, cur.pl.n_tok, p.c2, q4, m_run, l_run, O);
-    l_run += __shfl_xor(l_run, 16);
-    l_run += __shfl_xor(l_run, 32);
-    if (g < p.G) {
-      if (q4 == 0) { s_m[buf][wave][g] = m_run; s_l[buf][wave][g] = l_run; }
-      dec_stash<D>(s_o, wave, p.G, g, q4, O);
+    if (last_pass) {
+      const int lane = dec_lane_now(), g = lane & 15, q4 = lane >> 4;
+      float l_all = l_run + __shfl_xor(l_run, 16);
+      l_all += __shfl_xor(l_all, 32);
+      if (g < p.G) {
+        if (q4 == 0) { s_m[buf][wave][g] = m_run; s_l[buf][wave][g] = l_all; }
+        dec_stash<D>(s_o, wave, p.G, g, q4, O);
+      }
     }
-    // ---- the next item's bytes are requested before this one is merged ----
+    // ---- the next step's bytes are requested before this item is merged ----
     const item_t done = cur.it;
     cur = nxt; cur_page = nxt_page;
     request(cur, cur_page);
-    nxt = plan_of(w + 2 * stride, len2);
+    nxt = plan_of(st2, len2);
     nxt_page = *page_ptr(nxt);
-    len2 = p.kv_len[item_of(w + 3 * stride).b];
+    len2 = p.kv_len[item_of(st3.w).b];
+    if (!last_pass) continue;
     __syncthreads();     // the item's partials are in LDS; the other buffer is free again (its readers passed here)
+    ++n;
 
-    for (int e = tid; e < p.G * D; e += 64 * NW) {
+    for (int e = wave * 64 + dec_lane_now(); e < p.G * D; e += 64 * NW) {
       const int gg = e / D, d = e % D;
       float M = -INFINITY;
 #pragma unroll
@@ -662,13 +694,21 @@ int pa_launch_decode_bf16(const pa_decode_args& a) {
   p.fused = (a.n_split > 1 && a.n_split <= MAX_FUSED_SPLITS) ? 1 : 0;
   int n_cu = 1;
   pa_current_device(nullptr, &n_cu);
-  // Many more items than compute units, every row a single pass: persistent workgroups that keep bytes in flight
-  // across items, then the merge kernel.
+  // As many work items as compute units, or more: persistent workgroups that keep bytes in flight across items.
+  // With at least one (sequence, KV head) pair per compute unit a pair is one item, walked in passes of NW chunks, and the
+  // outputs are written by the same kernel; with fewer pairs but still four (sequence, KV head, split) items per
+  // compute unit the splits stay (one pass each, more items to balance) and the merge kernel follows.
   {
-    const int64_t items = (int64_t)a.batch * a.hkv * a.n_split;
+    const int64_t pairs = (int64_t)a.batch * a.hkv;
     const int64_t max_slots = (int64_t)powattn_max_k(&a.pat, a.capacity) * p.subs;
-    if (items >= 4 * (int64_t)n_cu && items <= 0x7fffffff / 4 && max_slots <= (int64_t)a.n_split * NW) {
+    int stream_splits = 0;
+    if (pairs >= (int64_t)n_cu) stream_splits = 1;
+    else if (pairs * a.n_split >= 4 * (int64_t)n_cu && max_slots <= (int64_t)a.n_split * NW) stream_splits = a.n_split;
+    const int64_t items = pairs * stream_splits;
+    if (stream_splits > 0 && items <= 0x7fffffff / 4 && max_slots <= 0x7fffffff / 4) {
       p.fused = 0;
+      p.splits = stream_splits;
+      const int n_pass = (int)((max_slots + (int64_t)stream_splits * NW - 1) / ((int64_t)stream_splits * NW));
       const size_t lds2 = 2 * (a.head_dim == 128 ? dec_o_bytes<128>(p.G) : dec_o_bytes<64>(p.G));   // at most 144 KB
       static std::atomic<unsigned long long> attr_done[2];
       const int which = a.head_dim == 128 ? 0 : 1;
@@ -677,11 +717,11 @@ int pa_launch_decode_bf16(const pa_decode_args& a) {
       if (int st = pa_allow_dynamic_lds(fn, 2 * (which == 0 ? dec_o_bytes<128>(MAXG) : dec_o_bytes<64>(MAXG)), attr_done[which])) return st;
       const dim3 pgrid((uint32_t)n_cu);
       if (a.head_dim == 128)
-        hipLaunchKernelGGL((pa_decode_stream_kernel<128>), pgrid, dim3(64 * NW), lds2, a.stream, p, (int)items);
+        hipLaunchKernelGGL((pa_decode_stream_kernel<128>), pgrid, dim3(64 * NW), lds2, a.stream, p, (int)items, n_pass);
       else
-        hipLaunchKernelGGL((pa_decode_stream_kernel<64>), pgrid, dim3(64 * NW), lds2, a.stream, p, (int)items);
+        hipLaunchKernelGGL((pa_decode_stream_kernel<64>), pgrid, dim3(64 * NW), lds2, a.stream, p, (int)items, n_pass);
       int st = pa_note_hip(hipGetLastError());
-      if (st != POWATTN_OK || a.n_split == 1) return st;
+      if (st != POWATTN_OK || stream_splits == 1) return st;
       dim3 mgrid((uint32_t)a.hq, (uint32_t)a.batch);
       if (a.head_dim == 128)
         hipLaunchKernelGGL((pa_decode_merge_kernel<128>), mgrid, dim3(64), 0, a.stream, p);

@@ -195,12 +195,17 @@ def test_more_splits_than_the_workgroups_merge_among_themselves():
     (64, 3, 2, 4, 4, 128, 1024, 300),      # one query head per KV head
     (64, 4, 1, 8, 4, 128, 512, 300),       # rows of at most 8 chunks: one split, outputs written without a merge kernel
     (64, 4, 1, 32, 2, 128, 1536, 260),     # 16 query heads per KV head: the largest LDS footprint
+    (64, 20, 1, 8, 4, 128, 4096, 300),     # rows of up to 26 chunks: a (sequence, KV head) pair is walked in four passes
+    (256, 5, 1, 4, 4, 64, 8192, 270),      # the paper's block size: four chunks per block, up to 40 chunks, five passes
+    (256, 6, 1, 4, 2, 64, 8192, 120),      # 240 pairs (fewer than compute units) of five splits: 1200 one-pass items + merge kernel
 ])
 def test_large_batches_on_persistent_workgroups(B, W, S, hq, hkv, d, cap, batch):
-    # With at least four work items (sequence, KV head, split) per compute unit and every row a single pass, the
-    # library streams the items through persistent workgroups (the next item's loads are issued before the
-    # current one is merged, lengths and pages are read ahead) and merges the splits in a second kernel.  Every
-    # sequence is checked, with lengths at both ends, around block boundaries and at random.
+    # With at least four work items (sequence, KV head, split) per compute unit the library streams the items through
+    # persistent workgroups (the next chunk's loads are issued before the current item is merged, lengths and pages
+    # are read ahead): with at least one (sequence, KV head) pair per compute unit a pair is one item walked in
+    # passes of eight chunks and the outputs come out of the same kernel; with fewer pairs the splits stay and a
+    # second kernel merges them.  Every sequence is checked, with lengths at both ends, around block boundaries and
+    # at random.
     pat = pa.Pattern(B, W, S)
     rng = np.random.default_rng(61)
     kv_len = rng.integers(1, cap + 1, size=batch)
