@@ -44,6 +44,7 @@ constexpr int PFD = 2;            // matrix instructions per group of LDS fragme
 constexpr int NSTG = 2;           // LDS stages of the tile stream: copies run NSTG-1 tiles ahead of the products (3 was
                                   // slower: the extra LDS halves the workgroups per compute unit at block 64)
 constexpr float LOG2E = 1.44269504088896340736f;
+constexpr int dq_stages(int) { return 2; }   // LDS stages of the dQ kernel's tile stream (see there)
 
 struct bwd_params {
   const __bf16* q; const __bf16* k; const __bf16* v; const __bf16* o; const __bf16* dout; const float* lse;
@@ -67,6 +68,11 @@ __device__ __forceinline__ void wait_vmcnt() {
 }
 __device__ __forceinline__ void async_copy16(const void* sbase, uint32_t voff, uint32_t lds_off) {
   asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_off) : "memory", "m0");
+}
+// the same with the LDS offset given as a scalar base plus a constant
+template <int OFF>
+__device__ __forceinline__ void async_copy16_at(const void* sbase, uint32_t voff, uint32_t lds_base) {
+  asm volatile("s_add_u32 m0, %2, %3\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_base), "n"(OFF) : "memory", "scc", "m0");
 }
 // one dword per lane: lane l's value lands at lds_off + 4*l
 __device__ __forceinline__ void async_copy4(const void* addr, uint32_t lds_off) {
@@ -98,6 +104,17 @@ struct tile_geo {
   static constexpr int V_KK = (16 / RPI) * SRB, V_DT = 4 * RPI * 16, V_HI = (8 / RPI) * SRB;
 };
 
+// copy instruction X of a wavefront's share of a tile, and the ones after it (instruction number wave + X * NWV)
+template <int D, int NWV, int X>
+__device__ __forceinline__ void copy_tile_unrolled(const __bf16* sb, int row0w, int lim, uint32_t chunk_off, uint32_t wdst) {
+  using G = tile_geo<D>;
+  if constexpr (X < G::IPT / NWV) {
+    int row = row0w + G::RPI * NWV * X;
+    row = row < lim ? row : lim;
+    async_copy16_at<X * NWV * G::SRB>(sb, (uint32_t)row * G::ROWB + chunk_off, wdst);
+    copy_tile_unrolled<D, NWV, X + 1>(sb, row0w, lim, chunk_off, wdst);
+  }
+}
 // Copies rows row0 .. row0+63 of a row-major [rows, D] array (rows beyond `last_row` repeat it) into the LDS tile
 // at `dst`; the NWV wavefronts of the workgroup share the tile's copy instructions.
 template <int D, int NWV>
@@ -107,11 +124,18 @@ __device__ __forceinline__ void copy_tile(const __bf16* base, int64_t row0, int6
   int64_t r0 = row0 < last_row ? row0 : last_row;
   const int lim = (int)(last_row - r0);
   const __bf16* sb = uniform_ptr(base + r0 * D);
-  for (int inst = wave; inst < G::IPT; inst += NWV) {
-    int row = G::RPI * inst + cp_row;
-    row = row < lim ? row : lim;
-    const uint32_t voff = (uint32_t)row * G::ROWB + (cp_chunk << 4);
-    async_copy16(sb, voff, __builtin_amdgcn_readfirstlane(dst + inst * G::SRB));
+  if constexpr (G::IPT % NWV == 0) {
+    // a known number of copy instructions per wavefront: straight-line code, LDS offsets as constants
+    const uint32_t wdst = __builtin_amdgcn_readfirstlane(dst + wave * G::SRB);
+    const int row0w = G::RPI * wave + cp_row;
+    copy_tile_unrolled<D, NWV, 0>(sb, row0w, lim, (uint32_t)(cp_chunk << 4), wdst);
+  } else {
+    for (int inst = wave; inst < G::IPT; inst += NWV) {
+      int row = G::RPI * inst + cp_row;
+      row = row < lim ? row : lim;
+      const uint32_t voff = (uint32_t)row * G::ROWB + (cp_chunk << 4);
+      async_copy16(sb, voff, __builtin_amdgcn_readfirstlane(dst + inst * G::SRB));
+    }
   }
 }
 // A operand "rows of the tile": rows 32rt + (lane%32), elements 16c + 8(lane/32) .. +7
@@ -205,10 +229,15 @@ __global__ __launch_bounds__(256) void pa_bwd_zero_kernel(float* p, int64_t n) {
 // dQ
 // ---------------------------------------------------------------------------------------------------------------
 template <int D, int NW>
-__global__ __launch_bounds__(64 * NW) void pa_bwd_dq_kernel(bwd_params p) {
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void pa_bwd_dq_kernel(bwd_params p) {
   using G = tile_geo<D>;
   constexpr int NC = G::NC, ND = G::ND;
   constexpr int STAGEB = 2 * G::TILEB;           // K tile then V tile
+  // LDS stages of the tile stream: the copies run NST-1 tiles ahead of the products.  Two: four stages for the
+  // workgroups of eight wavefronts (which have their compute unit to themselves anyway) were measured 5 % slower
+  // at the 128K workload, three halve the workgroups per compute unit at blocks of 64 keys.
+  constexpr int NST = dq_stages(NW);
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   __shared__ int s_tile[TILE_CAP];
   __shared__ int s_ntiles;
@@ -264,12 +293,12 @@ __global__ __launch_bounds__(64 * NW) void pa_bwd_dq_kernel(bwd_params p) {
   constexpr int CPF = 2 * G::IPT / NW;     // copies per wavefront and fill (K and V)
   auto fill = [&](int t) {
     const int key0 = s_tile[t];
-    const uint32_t dst = lds0 + (t % NSTG) * STAGEB;
+    const uint32_t dst = lds0 + (t % NST) * STAGEB;
     copy_tile<D, NW>(kslab, key0, p.N - 1, dst, wave, lane);
     copy_tile<D, NW>(vslab, key0, p.N - 1, dst + G::TILEB, wave, lane);
   };
   // the first tiles are requested before this wavefront's own rows: their copies would queue behind those loads
-  for (int s0 = 0; s0 < NSTG - 1; ++s0)
+  for (int s0 = 0; s0 < NST - 1; ++s0)
     if (s0 < n_tiles) fill(s0);
 
   bf16x8 qf[NC], dof[NC];
@@ -284,18 +313,17 @@ __global__ __launch_bounds__(64 * NW) void pa_bwd_dq_kernel(bwd_params p) {
   for (int dt = 0; dt < ND; ++dt)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[dt][r] = 0.f;
-  // Tile t has landed when only the fills of tiles t+1 .. t+NSTG-2 are outstanding (the counter retires in
-  // order).  Near the end, where fewer fills follow, wait for all.  (With two stages every wait is for all, the
-  // loads of Q and dO included.)
-  static_assert(NSTG == 2, "the row loads above are younger than the first fills: the waits must cover them");
+  // Tile t has landed when only the fills of tiles t+1 .. t+NST-2 are outstanding (the counter retires in
+  // order).  Near the end, where fewer fills follow, wait for all.  (The loads of Q and dO above are younger than
+  // the first fills; the compiler waits for them before their first use, which covers everything older.)
   for (int t = 0; t < n_tiles; ++t) {
-    if (t + NSTG - 1 <= n_tiles) wait_vmcnt<(NSTG - 2) * CPF>(); else wait_vmcnt<0>();
+    if (t + NST - 1 <= n_tiles) wait_vmcnt<(NST - 2) * CPF>(); else wait_vmcnt<0>();
     __syncthreads();                       // tile t has landed for everybody; everybody is done with tile t-1
-    if (t + NSTG - 1 < n_tiles) fill(t + NSTG - 1);      // into the stage tile t-1 has just left
+    if (t + NST - 1 < n_tiles) fill(t + NST - 1);        // into the stage tile t-1 has just left
     const int key0 = s_tile[t];
     // tiles that start beyond this wavefront's last query are masked out entirely for it
     if (!active || (int64_t)key0 > (int64_t)i * p.B + sl * 32 + 31) continue;
-    const uint32_t kt = lds0 + (t % NSTG) * STAGEB, vt = kt + G::TILEB;
+    const uint32_t kt = lds0 + (t % NST) * STAGEB, vt = kt + G::TILEB;
     f32x16 S[2], dP[2];
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt)
@@ -624,22 +652,30 @@ void pa_bwd_dkv_split_kernel(bwd_params p) {
     for (int r = 0; r < 16; ++r) acc[dt][r] = 0.f;
 
   const int n_tiles = n_ent * p.G * p.subs;
-  struct cursor_t { int u, gg, e; };
+  // The tiles of the column in order: the 64-query tiles of a query block, for each head of the group, for each
+  // entry of the column.  A cursor carries what a tile needs (query block, first query, first row of the head's
+  // slab, LDS stage) and moves on by additions: one runs ahead with the copies, one goes with the products.
+  struct cursor_t { int u, gg, e, i; int64_t q0, head_rows; uint32_t stage; };
   auto advance = [&](cursor_t& c) {
-    if (++c.u == p.subs) { c.u = 0; if (++c.gg == p.G) { c.gg = 0; ++c.e; } }
+    c.stage = c.stage == (NST - 1) * STAGEB ? 0u : c.stage + STAGEB;
+    if (++c.u < p.subs) { c.q0 += KT; return; }
+    c.u = 0;
+    if (++c.gg < p.G) { c.head_rows += p.N; }
+    else {
+      c.gg = 0;
+      c.head_rows -= (int64_t)(p.G - 1) * p.N;
+      if (++c.e < n_ent) c.i = entry(c.e);
+    }
+    c.q0 = (int64_t)c.i * p.B;
   };
-  auto locate = [&](const cursor_t& c, int& i, int& h, int64_t& q0) {
-    i = entry(c.e);
-    h = kvh * p.G + c.gg;
-    q0 = (int64_t)i * p.B + c.u * KT;
-  };
-  cursor_t cf = {0, 0, 0}, cc = {0, 0, 0};       // copies; this wavefront's products
-  auto fill = [&](int t) {
-    int i, h; int64_t q0;
-    locate(cf, i, h, q0);
+  cursor_t cf;                                   // the copies' cursor
+  cf.u = 0; cf.gg = 0; cf.e = 0; cf.i = entry(0); cf.q0 = (int64_t)cf.i * p.B;
+  cf.head_rows = ((int64_t)b * p.hq + (int64_t)kvh * p.G) * p.N; cf.stage = 0;
+  cursor_t cc = cf;                              // this wavefront's products
+  auto fill = [&]() {
+    const int64_t q0 = cf.q0, head_rows = cf.head_rows;
+    const uint32_t dst = lds0 + cf.stage;
     advance(cf);
-    const uint32_t dst = lds0 + (t % NST) * STAGEB;
-    const int64_t head_rows = ((int64_t)b * p.hq + h) * p.N;
     copy_tile<D, NW>(p.q + head_rows * D, q0, p.N - 1, dst, wave, lane);
     copy_tile<D, NW>(p.dout + head_rows * D, q0, p.N - 1, dst + G::TILEB, wave, lane);
     if (wave == 0) {
@@ -651,21 +687,21 @@ void pa_bwd_dkv_split_kernel(bwd_params p) {
     }
   };
   static_assert(G::IPT % NW == 0, "tile copies must divide over the wavefronts");
-  fill(0);
+  fill();
   // (after the first tile's copies: they would queue behind these row-per-lane loads)
   reg_rows<D>((krole ? p.v : p.k) + krow * D, kok, lane, xf);
   // iteration it: the P side works on tile it, the dS side on tile it-1
   for (int it = 0; it <= n_tiles; ++it) {
     wait_vmcnt<0>();
     __syncthreads();      // tile it has landed; P of tile it-1 is in LDS; everybody is done with tile it-2
-    if (it + 1 < n_tiles) fill(it + 1);
+    if (it + 1 < n_tiles) fill();                 // tile it+1
     const int t = krole ? it - 1 : it;
     if (t < 0 || t >= n_tiles) continue;          // uniform per wavefront; the barriers stay matched
-    int i, h; int64_t q0;
-    locate(cc, i, h, q0);
+    const int i = cc.i;
+    const int64_t q0 = cc.q0;
+    const uint32_t qt = lds0 + cc.stage, dot = qt + G::TILEB;
+    const float* vec = reinterpret_cast<const float*>(smem + cc.stage + 2 * G::TILEB);
     advance(cc);
-    const uint32_t qt = lds0 + (t % NST) * STAGEB, dot = qt + G::TILEB;
-    const float* vec = reinterpret_cast<const float*>(smem + (t % NST) * STAGEB + 2 * G::TILEB);
     const bool need_mask = i == j || q0 + KT > p.N || ((int64_t)j + 1) * p.B > p.N;
     unsigned char* pb = smem + NST * STAGEB + (t & 1) * PBUF + slice * 4096 + lane * 16;
 #pragma unroll
@@ -767,7 +803,7 @@ __global__ __launch_bounds__(256) void pa_bwd_sink_store_kernel(bwd_params p, in
 
 template <int D, int NW>
 int launch_dq(const bwd_params& p, int64_t items, hipStream_t stream) {
-  constexpr size_t lds = NSTG * 2 * (size_t)tile_geo<D>::TILEB;
+  constexpr size_t lds = dq_stages(NW) * 2 * (size_t)tile_geo<D>::TILEB;
   static std::atomic<unsigned long long> done{0};
   if (int st = pa_allow_dynamic_lds(reinterpret_cast<const void*>(&pa_bwd_dq_kernel<D, NW>), lds, done)) return st;
   hipLaunchKernelGGL((pa_bwd_dq_kernel<D, NW>), dim3((uint32_t)items), dim3(64 * NW), lds, stream, p);
@@ -818,7 +854,10 @@ int pa_launch_backward_bf16(const pa_backward_args& a) {
   const int64_t tasks = (int64_t)p.G * p.B / 32;
   if (tasks > (1 << 20)) return POWATTN_UNSUPPORTED;
   p.tasks = (int32_t)tasks;
-  const int nwq = p.tasks > 4 ? 8 : 4;
+  // eight wavefronts per workgroup when a query block has that many tasks and blocks of 128 keys or more; at
+  // blocks of 64 keys four (two workgroups per compute unit that are not in step with each other: 4-7 % faster
+  // at configuration 2's shape than one workgroup of eight)
+  const int nwq = (p.tasks > 4 && p.B >= 128) ? 8 : 4;
   p.chunks = (p.tasks + nwq - 1) / nwq;
   p.sink_blocks = a.pat.sink < a.nb ? a.pat.sink : a.nb;
   p.max_parts = p.sink_blocks > 0 ? (a.nb + PART - 1) / PART : 1;
