@@ -244,6 +244,8 @@ def main():
     dec_samples = time_batches(lambda s: pa.decode(pat_d, qd, *caches[s % len(caches)], lens, o=od, lse=lsed, workspace=ws),
                                20, 12, warm=4 * len(caches))
     decode_us = statistics.fmean(dec_samples)
+    # footnote: the same step on ONE cache over and over (54.5 MB: served by the 256 MB Infinity Cache after the first step)
+    dec_warm = time_batches(lambda s: pa.decode(pat_d, qd, *caches[0], lens, o=od, lse=lsed, workspace=ws), 20, 12, warm=12)
     row = pa.row_host(pat_d, (Dc["len"] - 1) // Dc["B"])
     decode_bytes = len(row) * Dc["B"] * Dc["d"] * 2 * 2 * Dc["hkv"] * Dc["batch"]   # attended K and V tokens
     decode_gbs = decode_bytes / (decode_us * 1e-6) / 1e9
@@ -556,6 +558,14 @@ def main():
         r1 = time.perf_counter()
         red_pairs = orc.attended_pairs(n_red, pat_r)
         red_flops = flops_block(64, 128, 4, 1, red_pairs)
+        # configuration 1 (the tiny fp32 one) in full, against the fp32 kernel's output
+        o1c, l1c = pa.prefill(pat_1, c_1, i_1, q1, k1, v1)
+        torch.cuda.synchronize()
+        t1a = time.perf_counter()
+        r1o, r1l = orc.attention(q1.cpu().numpy(), k1.cpu().numpy(), v1.cpu().numpy(), orc.Pattern(64, 2, 1))
+        t1b = time.perf_counter()
+        cfg1_err_o = float(np.abs(o1c.double().cpu().numpy() - r1o).max())
+        cfg1_err_l = float(np.abs(l1c.double().cpu().numpy() - r1l).max())
         c_r, i_r, _ = pa.mask_build(pa.Pattern(64, 4, 1), n_red)
         go_r, gl_r = pa.prefill(pa.Pattern(64, 4, 1), c_r, i_r, qr.to(dev), kr.to(dev), vr.to(dev))
         torch.cuda.synchronize()
@@ -566,7 +576,11 @@ def main():
                "full_tensor_reduced": {"shape": "b1, 4q/1kv heads, N=8192, D=128, block 64, W=4, S=1 (configuration 2 "
                                                 "cut to 8192 tokens and one KV head's group), every row",
                                        "seconds": round(r1 - r0, 2),
-                                       "value": red_flops / (r1 - r0) / 1e12, "unit": "TFLOP/s"}}
+                                       "value": red_flops / (r1 - r0) / 1e12, "unit": "TFLOP/s"},
+               "full_tensor_config1": {"shape": "b1, 2 heads, N=1024, D=64, block 64, W=2, S=1, fp32, every row",
+                                       "seconds": round(t1b - t1a, 4),
+                                       "value": flops_block(64, 64, 2, 1, int(c_1.sum().item())) / (t1b - t1a) / 1e12,
+                                       "unit": "TFLOP/s"}}
         go = og[:, :, rows_t.to(dev)].double().cpu().numpy()
         gl = lseg[:, :, rows_t.to(dev)].double().cpu().numpy()
         parity = {"attended_block_pairs_equal_oracle": True,
@@ -574,7 +588,8 @@ def main():
                   "prefill_max_abs_err_o": float(np.abs(go - oo).max()),
                   "prefill_max_abs_err_lse": float(np.abs(gl - olse).max()),
                   "prefill_reduced_full_tensor_max_abs_err_o": float(np.abs(go_r.double().cpu().numpy() - ro).max()),
-                  "prefill_reduced_full_tensor_max_abs_err_lse": float(np.abs(gl_r.double().cpu().numpy() - rl).max())}
+                  "prefill_reduced_full_tensor_max_abs_err_lse": float(np.abs(gl_r.double().cpu().numpy() - rl).max()),
+                  "config1_fp32_max_abs_err_o": cfg1_err_o, "config1_fp32_max_abs_err_lse": cfg1_err_l}
         # the decode step that was timed: three sequences of the cache of the last timed step
         kc, vc = caches[(args.steps - 1) % len(caches)]
         pa.decode(pat_d, qd, kc, vc, lens, o=od, lse=lsed, workspace=ws)
@@ -631,6 +646,7 @@ def main():
         "decode": {"tokens_per_s": round(Dc["batch"] / (decode_us * 1e-6), 1), "us_per_step": round(decode_us, 2),
                    "us_per_step_stats": stats(dec_samples),
                    "in_step_us": round(decode_in_step_us, 2), "in_step_us_stats": stats(decode_in_step),
+                   "warm_same_cache_us_per_step": stats(dec_warm),
                    "steps_timed": 20 * 12,
                    "roofline": {"bound": "hbm", "kernel": "pa_decode_kernel", "achieved": round(decode_gbs, 1),
                                 "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(decode_gbs / PEAK_HBM_GBS, 4),
