@@ -65,6 +65,56 @@ def test_config4_shape_reduced_batch():
     run_decode(pa.Pattern(64, 4, 1), 2, 32, 8, 65536, 128, [65536, 65535], seed=3)
 
 
+def test_context_of_131072_tokens():
+    # the metric's context length: 14 attended blocks per row (one more power-of-two distance than at 65536)
+    run_decode(pa.Pattern(64, 4, 1), 2, 32, 8, 131072, 128, [131072, 131071 - 64], seed=4)
+
+
+def test_decode_replayed_from_a_hip_graph():
+    # The call keeps no per-call state on the host (the generation numbers of the merge live in the workspace), so
+    # a captured launch can be replayed: capture one decode step per entry point, replay each several times with
+    # eager calls on the same inputs and changed inputs in between, and compare every replay with the eager result.
+    pat = pa.Pattern(64, 4, 1)
+    batch, hq, hkv, cap, d = 4, 8, 2, 8192, 128
+    q, k, v = synth.decode_inputs(batch, hq, hkv, cap, d, "bf16", 91)
+    q2 = synth.decode_inputs(batch, hq, hkv, cap, d, "bf16", 92)[0]
+    lens = torch.tensor([8192, 5000, 4097, 130], dtype=torch.int32).cuda()
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    ws = pa.decode_workspace(pat, batch, hq, hkv, d, cap)
+    ref1, rl1 = pa.decode(pat, qd, kd, vd, lens)
+    ref2, rl2 = pa.decode(pat, q2.cuda(), kd, vd, lens)
+    torch.cuda.synchronize()
+    ref1, rl1, ref2, rl2 = ref1.clone(), rl1.clone(), ref2.clone(), rl2.clone()
+    qs = qd.clone()                                    # static input of the graphs
+    o_g = torch.empty_like(qd); l_g = torch.empty((batch, hq), dtype=torch.float32, device="cuda")
+    o_s = torch.empty_like(qd); l_s = torch.empty((batch, hq), dtype=torch.float32, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm up on the capture stream (one-time launch set-up)
+        pa.decode(pat, qs, kd, vd, lens, o=o_g, lse=l_g, workspace=ws, stream=side)
+        pa.decode_static(pat, qs, kd, vd, lens, o_s, l_s, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g1, g2 = torch.cuda.CUDAGraph(), torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g1):
+        pa.decode(pat, qs, kd, vd, lens, o=o_g, lse=l_g, workspace=ws)
+    with torch.cuda.graph(g2):
+        pa.decode_static(pat, qs, kd, vd, lens, o_s, l_s)
+    for rep in range(6):
+        src, want, want_l = (qd, ref1, rl1) if rep % 2 == 0 else (q2.cuda(), ref2, rl2)
+        qs.copy_(src)
+        o_g.fill_(float("nan")); o_s.fill_(float("nan"))
+        g1.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(o_g, want) and torch.equal(l_g, want_l), rep
+        # eager work of the program between the replays, on the same workspace and on the library's own buffer
+        e, _ = pa.decode(pat, src, kd, vd, lens, workspace=ws)
+        assert torch.equal(e, want)
+        g2.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(o_s, want) and torch.equal(l_s, want_l), rep
+
+
 def test_decode_equals_prefill_row():
     pat = pa.Pattern(64, 4, 1)
     n, hq, hkv, d = 2048, 8, 2, 128
