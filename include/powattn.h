@@ -144,7 +144,8 @@ int powattn_prefill(const powattn_pattern* pattern,
  *   q, o           device [batch, n_q_heads, q_len, head_dim]
  *   k_cache, v_cache  device [batch, n_kv_heads, cache_capacity, head_dim]
  *   lse            device float [batch, n_q_heads, q_len] or NULL
- *   q_start        a multiple of pattern->block; q_start + q_len <= cache_capacity
+ *   q_start        any position >= 0 (a chunk may start and end inside a block);
+ *                  q_start + q_len <= cache_capacity
  *   dtype          POWATTN_BF16 only; head_dim 64 or 128; block a multiple of 64, at most 1024
  * Errors: INVALID_ARG, UNSUPPORTED, HIP_ERROR.
  */

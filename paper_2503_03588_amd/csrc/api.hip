@@ -142,7 +142,6 @@ extern "C" int powattn_prefill_chunk(const powattn_pattern* pattern,
   if (q_start < 0 || q_len < 1 || cache_capacity < 1 || q_start > INT64_MAX - q_len) return POWATTN_INVALID_ARG;
   if (q_start + q_len > cache_capacity) return POWATTN_INVALID_ARG;
   if (n_q_heads % n_kv_heads != 0) return POWATTN_INVALID_ARG;
-  if (q_start % pattern->block != 0) return POWATTN_INVALID_ARG;      // query blocks must be pattern blocks
   const bool dense = (pattern->flags & POWATTN_DENSE) != 0;
   if (!dense && (!d_kv_cnt || !d_kv_idx || max_k < 1)) return POWATTN_INVALID_ARG;
   const int64_t seq_len = q_start + q_len;
@@ -159,7 +158,8 @@ extern "C" int powattn_prefill_chunk(const powattn_pattern* pattern,
   a.q = q; a.k = k_cache; a.v = v_cache; a.o = o; a.lse = lse;
   a.batch = batch; a.hq = n_q_heads; a.hkv = n_kv_heads;
   a.seq_len = seq_len; a.q_start = q_start; a.kv_rows = cache_capacity; a.q_rows = 0; a.seq_len_dev = nullptr;
-  a.nb = (int32_t)((q_len + pattern->block - 1) / pattern->block);
+  // query blocks are the pattern's blocks: the first one is partial when the chunk starts inside a block
+  a.nb = (int32_t)((seq_len + pattern->block - 1) / pattern->block - q_start / pattern->block);
   a.head_dim = head_dim;
   a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)head_dim);
   a.stream = (hipStream_t)hip_stream;

@@ -83,7 +83,7 @@ struct bf16_params {
   int32_t chain;     // items may be chained in persistent workgroups
   int64_t total_wg;
   int64_t N;         // keys in the context: query q_start + r attends keys <= q_start + r, all of them < N
-  int64_t q_start;   // position of the first query row of Q/O (a multiple of B); 0 for a whole-sequence prefill
+  int64_t q_start;   // position of the first query row of Q/O (anywhere inside block i0); 0 for a whole-sequence prefill
   int64_t q_rows;    // rows of Q/O per head (N - q_start)
   int64_t kv_rows;   // rows per (batch, KV head) slab of K/V (N, or the capacity of a cache)
   int32_t i0;        // first query block: q_start / B
@@ -403,7 +403,7 @@ void pa_prefill_bf16_kernel(bf16_params p) {
 #pragma unroll
     for (int m = 0; m < NC; ++m) {
       const int rho = m / QE, e = m % QE;
-      const bool ok = act && tok0 + rho < keys_of(it);
+      const bool ok = act && tok0 + rho < keys_of(it) && tok0 + rho >= p.q_start;   // (a chunk may start inside a block)
       qraw[m] = ok ? *reinterpret_cast<const u32x4*>(qbase + (int64_t)rho * D + 32 * e) : u32x4{0, 0, 0, 0};
     }
   };
@@ -844,11 +844,11 @@ void pa_prefill_bf16_kernel(bf16_params p) {
 #pragma unroll
         for (int k2 = 0; k2 < 4; ++k2) {
           const u32x4 wv = {c[k2][0], c[k2][1], c[k2][2], c[k2][3]};
-          if (active && tok0 + k2 < keys_of(it))
+          if (active && tok0 + k2 < keys_of(it) && tok0 + k2 >= p.q_start)
             *reinterpret_cast<u32x4*>(obase + (int64_t)k2 * D + 32 * u) = wv;
         }
       }
-      if (active && tok < keys_of(it) && p.lse && hh == 0)
+      if (active && tok < keys_of(it) && tok >= p.q_start && p.lse && hh == 0)
         p.lse[((int64_t)it.b * p.hq + h) * p.q_rows + (tok - p.q_start)] = (m_run + log2f(ltot)) * 0.69314718055994530942f;
     }
     it = it1; it1 = it2; it2 = VARLEN ? next_valid(it2, raw2) : next_item(it2);

@@ -132,7 +132,6 @@ def test_prefill_chunk_argument_errors(L):
     assert _chunk(L, max_k=0) == pa.INVALID_ARG
     assert _chunk(L, hq=6, hkv=4) == pa.INVALID_ARG
     assert _chunk(L, q_start=-64) == pa.INVALID_ARG
-    assert _chunk(L, q_start=1000) == pa.INVALID_ARG             # not a multiple of the block size
     assert _chunk(L, q_len=0) == pa.INVALID_ARG
     assert _chunk(L, q_start=4032, q_len=128) == pa.INVALID_ARG  # runs past the cache capacity
     assert _chunk(L, scale=float("nan")) == pa.INVALID_ARG

@@ -30,6 +30,10 @@ def caches_from(k, v, cap):
     (2048, 64, 3, 1, 4, 2, 64, 1, 2048, [0, 1024, 2048], 0),                      # sliding window, head_dim 64
     (2048, 64, 1, 0, 4, 2, 128, 1, 4096, [0, 512, 2048], pa.DENSE),               # dense
     (1900, 192, 2, 1, 4, 2, 128, 1, 2304, [0, 768, 1900], pa.POWER),              # blocks of 192 tokens
+    (4096, 64, 4, 1, 8, 2, 128, 1, 4096, [0, 1000, 1001, 1023, 1100, 3003, 4096], pa.POWER),   # cuts inside blocks
+    (3000, 128, 2, 1, 6, 2, 128, 2, 3000, [0, 129, 255, 2049, 3000], pa.POWER),   # the same with two tiles per block, ragged end
+    (2500, 64, 3, 1, 4, 2, 64, 1, 2560, [0, 7, 1999, 2500], 0),                   # sliding window, head_dim 64, unaligned cuts
+    (2048, 64, 1, 0, 4, 2, 128, 1, 2048, [0, 500, 2048], pa.DENSE),               # dense, unaligned cut
 ])
 def test_chunks_equal_whole_prefill(n, B, W, S, hq, hkv, d, batch, cap, cuts, flags):
     pat = pa.Pattern(B, W, S, flags)
