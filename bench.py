@@ -36,9 +36,9 @@ PEAK_HBM_GBS = 8000.0            # MI355X HBM3E peak
 # the kernel and the grid it was taken on (profiles/*.md hold the runs); it is reported only while the library
 # that is loaded still has that version (the version number moves with every change to a kernel), else null.
 TRAFFIC = {
-    "prefill": {"bytes": 5.42e9, "library_version": 104, "kernel": "pa_prefill_bf16_kernel<128,8,4,false,true,false>",
+    "prefill": {"bytes": 5.42e9, "library_version": 105, "kernel": "pa_prefill_bf16_kernel<128,8,4,false,true,false,false>",
                 "grid": 256, "source": "profiles/prefill_bf16_128k_pmc.md"},
-    "decode": {"bytes": 57.6e6, "library_version": 104, "kernel": "pa_decode_kernel<128>", "grid": [2, 8, 16],
+    "decode": {"bytes": 57.6e6, "library_version": 105, "kernel": "pa_decode_kernel<128>", "grid": [2, 8, 16],
                "source": "profiles/decode_b16_64k_pmc.md"},
 }
 
@@ -452,6 +452,25 @@ def main():
                                  dvg[:, :1].double().cpu().numpy())
         del dog, dqg, dkg, dvg, wsb
 
+    # ---------------- the configuration-3 prompt against a paged KV cache (powattn_prefill_chunk_paged: pages of one
+    # block each, shuffled over a pool, found through a block table); same tensors, result compared bit for bit ----
+    paged_prefill = None
+    if not args.no_dense:
+        nbk = P["n"] // P["B"]
+        perm = torch.from_numpy(np.random.default_rng(6000).permutation(nbk + 17)[:nbk].astype(np.int64)).to(dev)
+        kp = torch.zeros(nbk + 17, P["hkv"], P["B"], P["d"], device=dev, dtype=torch.bfloat16)
+        vp = torch.zeros_like(kp)
+        kp[perm] = kg[0].reshape(P["hkv"], nbk, P["B"], P["d"]).permute(1, 0, 2, 3)
+        vp[perm] = vg[0].reshape(P["hkv"], nbk, P["B"], P["d"]).permute(1, 0, 2, 3)
+        table_p = perm.to(torch.int32).reshape(1, nbk).contiguous()
+        o_pg, lse_pg = torch.empty_like(qg), torch.empty_like(lseg)
+        pa.prefill(pat_p, cnt, idx, qg, kg, vg, o=og, lse=lseg)
+        ms_pg = stats(time_launches(lambda s: pa.prefill_chunk_paged(pat_p, cnt, idx, qg, kp, vp, table_p, 0, o=o_pg, lse=lse_pg), 20, 5))
+        paged_prefill = {"workload": "configuration 3 with K/V in a shuffled pool of %d pages of %d tokens" % (nbk + 17, P["B"]),
+                         "kernel_ms": ms_pg, "tflops": round(f_block / (ms_pg["mean"] * 1e-3) / 1e12, 1),
+                         "bit_identical_to_contiguous": bool(torch.equal(o_pg, og) and torch.equal(lse_pg, lseg))}
+        del kp, vp, o_pg, lse_pg
+
     # ---------------- a serving batch of prompts of different lengths in one launch (powattn_prefill_varlen,
     # lengths in device memory): 64 prompts of 512..8192 tokens, configuration 2's heads and pattern ----------------
     varlen = None
@@ -660,6 +679,7 @@ def main():
         "paper_setting_b256_w5_s1": sweep,
         "layer_stack": stack,
         "prefill_varlen_batch": varlen,
+        "prefill_paged_cache": paged_prefill,
         "backward_128k": backward,
         "prefill_sustained": sustained,
         "parity": parity,

@@ -157,6 +157,40 @@ int powattn_prefill_chunk(const powattn_pattern* pattern,
                           int32_t head_dim, int32_t dtype, float softmax_scale, void* hip_stream);
 
 /*
+ * powattn_prefill_chunk over a paged KV cache (the layout of powattn_decode_paged):
+ * a piece of a prompt is processed against keys and values that live in pages of
+ * one block each, which is how a serving system that decodes from pages (Section
+ * 4.3: prefill plus decode steps end to end) also has to prefill.  The result is,
+ * bit for bit, that of powattn_prefill_chunk on the contiguous cache the pages
+ * spell out.
+ *   q, o              device [batch, n_q_heads, q_len, head_dim], rows = positions
+ *                     q_start .. q_start+q_len-1 (q_start anywhere, also inside a block)
+ *   lse               device [batch, n_q_heads, q_len] fp32, or null
+ *   k_pages, v_pages  device [n_pages, n_kv_heads, block, head_dim]; positions
+ *                     0 .. q_start+q_len-1 of every sequence must be filled in
+ *   d_block_table     device int32 [batch, table_stride]: entry [b][j] is the page of
+ *                     tokens j*block .. (j+1)*block-1 of sequence b; a page number
+ *                     outside [0, n_pages) is clamped into the pool by the kernel
+ *                     (wrong numbers, no stray access); q_start+q_len <= table_stride*block
+ *   d_kv_cnt, d_kv_idx, max_k   the block lists, indexed by the block number in the
+ *                     sequence (built for at least q_start+q_len tokens)
+ *   dtype             POWATTN_BF16 only; head_dim 64 or 128; block a multiple of 64, at
+ *                     most 1024; max_k <= 63 and max_k * block / 64 <= 1024;
+ *                     n_pages * n_kv_heads * block < 2^31.  POWATTN_DENSE is not
+ *                     supported here (UNSUPPORTED): copy the pages out, or decode.
+ * One kernel launch; allocates nothing.
+ * Errors: INVALID_ARG, UNSUPPORTED, HIP_ERROR.
+ */
+int powattn_prefill_chunk_paged(const powattn_pattern* pattern,
+                                const int32_t* d_kv_cnt, const int32_t* d_kv_idx, int32_t max_k,
+                                const void* q, const void* k_pages, const void* v_pages,
+                                const int32_t* d_block_table, int32_t table_stride, int64_t n_pages,
+                                void* o, float* lse,
+                                int32_t batch, int32_t n_q_heads, int32_t n_kv_heads,
+                                int64_t q_start, int64_t q_len,
+                                int32_t head_dim, int32_t dtype, float softmax_scale, void* hip_stream);
+
+/*
  * powattn_prefill for a batch of sequences of different lengths (what a serving
  * batch of prompts looks like; Section 4.3 measures end-to-end generation), in
  * ONE launch, with the lengths in device memory (no host copy, no

@@ -5,7 +5,7 @@
 #include "../../include/powattn.h"
 #include "pattern.h"
 
-#define POWATTN_VERSION_NUMBER 104  // 0.1.4; moves with every change to a kernel (bench.py ties its profiled traffic figures to it)
+#define POWATTN_VERSION_NUMBER 105  // 0.1.5; moves with every change to a kernel (bench.py ties its profiled traffic figures to it)
 
 // Records a HIP error for powattn_strerror and maps it to a status.
 int pa_note_hip(hipError_t e);
@@ -32,6 +32,10 @@ struct pa_prefill_args {
   int64_t q_rows;    // rows per (batch, query head) slab of Q/O/LSE; 0: seq_len - q_start
   int32_t nb;      // query blocks: ceil((seq_len - q_start) / block)
   const int32_t* seq_len_dev;   // device [batch]: every sequence's own length, seq_len then being the padded one; or null
+  // paged KV cache (k, v are then page pools [n_pages, hkv, block, head_dim]); null: contiguous slabs of kv_rows rows
+  const int32_t* block_table = nullptr;   // device [batch, table_stride]: page of every block of every sequence
+  int32_t table_stride = 0;
+  int64_t n_pages = 0;
   int32_t head_dim;
   float scale;     // softmax scale (natural units)
   hipStream_t stream;

@@ -89,6 +89,8 @@ struct bf16_params {
   int32_t i0;        // first query block: q_start / B
   float c2;          // softmax scale * log2(e)
   const int32_t* seq_len;   // padded batch of sequences of different lengths: device array [batch]; N is then the padded length
+  const int32_t* block_table;   // paged cache: device [batch, table_stride], page of every block; k, v are the page pools
+  int32_t table_stride, n_pages;
 };
 
 // The work of one query block is a sequence of 64-key tiles: the tiles of the listed blocks before
@@ -130,8 +132,10 @@ __device__ __forceinline__ void wait_vmcnt() {   // s_waitcnt vmcnt(N) only
 // DENSE: the implicit list {0..i} instead of a block list.  CHAIN: the launch chains work items in persistent
 // workgroups (two half-size tile tables, list rows prefetched); otherwise one workgroup per item.  VARLEN: every
 // sequence of the batch has its own length, read from device memory; the work items are numbered as if all had the
-// padded length, and a workgroup passes over the items of query blocks that a sequence does not have.
-template <int D, int NW, int NS, bool DENSE, bool CHAIN, bool VARLEN>
+// padded length, and a workgroup passes over the items of query blocks that a sequence does not have.  PAGED: K and V
+// are pools of pages of one block each; the tile table then also holds every tile's first row in the pool, looked up
+// in the sequence's block table when the table is written (explicit lists, chained items only).
+template <int D, int NW, int NS, bool DENSE, bool CHAIN, bool VARLEN, bool PAGED>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void pa_prefill_bf16_kernel(bf16_params p) {
   constexpr int ROWB = 2 * D;        // bytes per K/V row
@@ -178,7 +182,9 @@ void pa_prefill_bf16_kernel(bf16_params p) {
   }
   if (n_raw == 0) return;
   constexpr bool chained = CHAIN;      // tables in halves, list rows prefetched
-  constexpr int tab_half = CHAIN ? TILE_CAP / 2 : 0;
+  constexpr int tab_half = CHAIN ? (PAGED ? TILE_CAP / 4 : TILE_CAP / 2) : 0;
+  constexpr int PHYS = TILE_CAP / 2;   // paged: entry e's first pool row sits at s_tile[PHYS + e]
+  static_assert(!PAGED || (CHAIN && !DENSE && !VARLEN), "paged caches: explicit lists, chained items");
 
   // Items are numbered L = ((b*hkv + kvh)*nb + r)*chunks + chunk with r counting query blocks from the last one
   // down (longest rows first, which matters for the dense list).  The first item is decoded by division, the
@@ -238,24 +244,44 @@ void pa_prefill_bf16_kernel(bf16_params p) {
   // Writes the table of an item from its list row: lane e holds entry e (j), n entries in all; the tiles of the
   // blocks before the diagonal one in list order (ranks by a prefix count over the lanes), then the diagonal ones.
   // Called by the first wavefront, once per 64 entries.
-  auto table_rows = [&](int tab, const item_t& it, int j, int& blocks, bool& has_diag) {
+  // (paged: `page` is the page of the lane's block j, `page_i` that of the diagonal block)
+  auto pool_row = [&](const item_t& it, int page) -> int {   // first row of a page's slab for the item's KV head
+    page = page < 0 ? 0 : (page >= p.n_pages ? p.n_pages - 1 : page);
+    return (page * p.hkv + it.kvh) * p.B;
+  };
+  auto table_rows = [&](int tab, const item_t& it, int j, int page, int& blocks, bool& has_diag) {
     const bool valid = j >= 0 && j < it.i;                  // not padding, causal, not the diagonal block
     const uint64_t vm = __builtin_amdgcn_ballot_w64(valid);
     has_diag = has_diag || __builtin_amdgcn_ballot_w64(j == it.i) != 0;
     const int rank = blocks + (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(vm >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)vm, 0));
     if (valid)
-      for (int u = 0; u < p.subs; ++u) s_tile[tab * tab_half + rank * p.subs + u] = j * p.B + u * KT;
+      for (int u = 0; u < p.subs; ++u) {
+        s_tile[tab * tab_half + rank * p.subs + u] = j * p.B + u * KT;
+        if (PAGED) s_tile[PHYS + tab * tab_half + rank * p.subs + u] = pool_row(it, page) + u * KT;
+      }
     blocks += __builtin_popcountll(vm);
   };
-  auto table_finish = [&](int tab, const item_t& it, int blocks, bool has_diag) {
+  auto table_finish = [&](int tab, const item_t& it, int page_i, int blocks, bool has_diag) {
     int w = blocks * p.subs;
     if (lane == 0) s_cnt[tab][1] = w;
     if (has_diag) {
-      if (lane < it.subs_diag) s_tile[tab * tab_half + w + lane] = it.i * p.B + lane * KT;
+      if (lane < it.subs_diag) {
+        s_tile[tab * tab_half + w + lane] = it.i * p.B + lane * KT;
+        if (PAGED) s_tile[PHYS + tab * tab_half + w + lane] = pool_row(it, page_i) + lane * KT;
+      }
       w += it.subs_diag;
     }
     if (lane == 0) s_cnt[tab][0] = w;
-    if (w == 0 && lane == 0) s_tile[tab * tab_half] = 0;   // an empty row still has an entry to look up
+    if (w == 0 && lane == 0) {                              // an empty row still has an entry to look up
+      s_tile[tab * tab_half] = 0;
+      if (PAGED) s_tile[PHYS + tab * tab_half] = 0;
+    }
+  };
+  // the page of block j of the item's sequence (any j: the index is clamped into the table)
+  auto page_of = [&](const item_t& it, int j) -> int {
+    if (!PAGED) return 0;
+    j = j < 0 ? 0 : (j >= p.table_stride ? p.table_stride - 1 : j);
+    return p.block_table[(int64_t)it.b * p.table_stride + j];
   };
   auto table_from_memory = [&](int tab, const item_t& it) {          // first wavefront
     int n = p.kv_cnt[it.i];
@@ -266,19 +292,24 @@ void pa_prefill_bf16_kernel(bf16_params p) {
     for (int base = 0; base < n; base += 64) {
       const int e = base + lane;
       const int j = e < n ? p.kv_idx[(int64_t)it.i * p.max_k + e] : -1;
-      table_rows(tab, it, j, blocks, has_diag);
+      table_rows(tab, it, j, page_of(it, j), blocks, has_diag);
     }
-    table_finish(tab, it, blocks, has_diag);
+    table_finish(tab, it, page_of(it, it.i), blocks, has_diag);
   };
-  auto table_from_row = [&](int tab, const item_t& it) {             // first wavefront; row copied earlier into s_raw[0]
+  // first wavefront; the row was copied earlier into s_raw[0].  Paged: the pages of the row's blocks are requested by
+  // row_pages at the start of an item and used here, after the Q fragments have been arranged.
+  auto row_entry = [&]() -> int {
     int n = __builtin_amdgcn_readfirstlane(s_raw[0][63]);
     if (n > p.max_k) n = p.max_k;
     const int raw = s_raw[0][lane];
-    const int j = lane < n ? raw : -1;
+    return lane < n ? raw : -1;
+  };
+  auto table_from_row = [&](int tab, const item_t& it, int page, int page_i) {
+    const int j = row_entry();
     int blocks = 0;
     bool has_diag = false;
-    table_rows(tab, it, j, blocks, has_diag);
-    table_finish(tab, it, blocks, has_diag);
+    table_rows(tab, it, j, page, blocks, has_diag);
+    table_finish(tab, it, page_i, blocks, has_diag);
   };
   // Asynchronous copy of the list row of item k into this wavefront's s_raw (every wavefront issues it, so
   // that all of them count the same number of outstanding copies; only the first one's copy is read).
@@ -307,14 +338,16 @@ void pa_prefill_bf16_kernel(bf16_params p) {
 #pragma unroll
   for (int x = 0; x < IPW; ++x) f_row[x] = RPI * (wave * IPW + x) + cp_row;
   const uint32_t f_chunk = (uint32_t)cp_chunk << 4;
-  auto fill_prep = [&](const __bf16* kbase, const __bf16* vbase, int key0, uint32_t dst) {
+  auto fill_prep = [&](const __bf16* kbase, const __bf16* vbase, int key0, int phys0, uint32_t dst) {
     // ragged tail: rows beyond the sequence repeat its last row (they are masked, but must be finite)
     const int last = (VARLEN ? c_n : (int)p.N) - 1;   // of the sequence whose tiles the cursor is copying
     const int k0 = key0 < last ? key0 : last;
     f_lim = last - k0;
+    // paged: the tile's rows in the pool (a tile that starts beyond the sequence lies in the page of its last key)
+    const int64_t row0 = PAGED ? (int64_t)phys0 + (k0 - key0) : (int64_t)k0;
     // (scalar values may live in vector registers when scalar registers are short: pin the bases down)
-    f_kt = uniform_ptr(kbase + (int64_t)k0 * D);
-    f_vt = uniform_ptr(vbase + (int64_t)k0 * D);
+    f_kt = uniform_ptr(kbase + row0 * D);
+    f_vt = uniform_ptr(vbase + row0 * D);
     f_dst = dst;
   };
   auto fill_copy = [&](auto jc) {                      // copy j of LPT: instruction x = j/2 of this wavefront, K then V
@@ -346,6 +379,7 @@ void pa_prefill_bf16_kernel(bf16_params p) {
   uint32_t c_dst = w_dst;       // this wavefront's share of the stage the next fill goes to
   uint32_t c_tab = 0;           // LDS address of the table the cursor reads
   int pref_key = 0;             // table entry of the cursor's position, read from LDS one fill ahead of its use
+  int pref_phys = 0;            // paged: the same entry's first pool row
   const __bf16* c_kb = p.k;
   const __bf16* c_vb = p.v;
   auto cursor_enter = [&](int k, const item_t& it) {
@@ -356,10 +390,13 @@ void pa_prefill_bf16_kernel(bf16_params p) {
     if (!DENSE) {
       c_tab = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) int*)&s_tile[(k & 1) * tab_half]);
       pref_key = s_tile[(k & 1) * tab_half];
+      if (PAGED) pref_phys = s_tile[PHYS + (k & 1) * tab_half];
     }
     c_steps = (k + 1 < n_items && c_ntiles < MIN_STEPS) ? MIN_STEPS : c_ntiles;
-    c_kb = p.k + (((int64_t)it.b * p.hkv + it.kvh) * p.kv_rows) * D;
-    c_vb = p.v + (((int64_t)it.b * p.hkv + it.kvh) * p.kv_rows) * D;
+    if (!PAGED) {                // (paged: the pools' bases, set once)
+      c_kb = p.k + (((int64_t)it.b * p.hkv + it.kvh) * p.kv_rows) * D;
+      c_vb = p.v + (((int64_t)it.b * p.hkv + it.kvh) * p.kv_rows) * D;
+    }
   };
   // Prepares the next fill of the stream.  After the end of the stream the fills go on, re-reading the last
   // tile of the last item into stages nobody reads: every step then issues the same number of copies, and
@@ -372,11 +409,14 @@ void pa_prefill_bf16_kernel(bf16_params p) {
     int key0;
     if (DENSE) key0 = (c_pos < c_last ? c_pos : c_last) * KT;
     else key0 = __builtin_amdgcn_readfirstlane(pref_key);
-    fill_prep(c_kb, c_vb, key0, c_dst);
+    fill_prep(c_kb, c_vb, key0, PAGED ? __builtin_amdgcn_readfirstlane(pref_phys) : 0, c_dst);
     c_dst = c_dst == w_dst + (NS - 1) * STAGEB ? w_dst : c_dst + STAGEB;
     ++c_pos;
-    if (!DENSE)
-      pref_key = *reinterpret_cast<const __attribute__((address_space(3))) int*>((uintptr_t)(c_tab + 4 * (uint32_t)(c_pos < c_last ? c_pos : c_last)));
+    if (!DENSE) {
+      const uint32_t at = c_tab + 4 * (uint32_t)(c_pos < c_last ? c_pos : c_last);
+      pref_key = *reinterpret_cast<const __attribute__((address_space(3))) int*>((uintptr_t)at);
+      if (PAGED) pref_phys = *reinterpret_cast<const __attribute__((address_space(3))) int*>((uintptr_t)(at + 4 * PHYS));
+    }
   };
   auto fill_all = [&]() {
 #pragma unroll
@@ -575,12 +615,18 @@ void pa_prefill_bf16_kernel(bf16_params p) {
     // with a wait that would also drain the asynchronous copies.
 #pragma unroll
     for (int c = 0; c < NC; ++c) asm volatile("" : "+v"(qraw[c]));
+    // paged: the pages of the next item's blocks are requested here and used below, behind the arranging of Q
+    int nx_page = 0, nx_page_i = 0;
+    if (PAGED && wave == 0 && k >= 1 && more) {
+      nx_page = page_of(it1, row_entry());
+      nx_page_i = page_of(it1, it1.i);
+    }
     q_arrange();
 
     // ---- look-ahead: the table of the next item from its prefetched list row (the first two tables were
     // built above), and the copy of the row of the item after it ----
     if (chained) {
-      if (!DENSE && wave == 0 && k >= 1 && more) table_from_row((k + 1) & 1, it1);
+      if (!DENSE && wave == 0 && k >= 1 && more) table_from_row((k + 1) & 1, it1, nx_page, nx_page_i);
       copy_row(k + 2 < n_items ? it2 : it);
     }
 
@@ -857,11 +903,11 @@ void pa_prefill_bf16_kernel(bf16_params p) {
   wait_vmcnt<0>();
 }
 
-template <int D, int NW, int NS, bool DENSE, bool CHAIN, bool VARLEN>
+template <int D, int NW, int NS, bool DENSE, bool CHAIN, bool VARLEN, bool PAGED = false>
 int launch_as(const bf16_params& p, hipStream_t stream) {
   constexpr size_t lds = (size_t)NS * 2 * (KT / (512 / D)) * (1024 + 16 * (512 / D));
   static std::atomic<unsigned long long> attr_done{0};
-  if (int st = pa_allow_dynamic_lds(reinterpret_cast<const void*>(&pa_prefill_bf16_kernel<D, NW, NS, DENSE, CHAIN, VARLEN>), lds, attr_done))
+  if (int st = pa_allow_dynamic_lds(reinterpret_cast<const void*>(&pa_prefill_bf16_kernel<D, NW, NS, DENSE, CHAIN, VARLEN, PAGED>), lds, attr_done))
     return st;
   // One workgroup per work item, or, when the items can be chained (the block lists are short enough for the
   // look-ahead tables and registers), one persistent workgroup per compute unit that walks through its share.
@@ -873,12 +919,13 @@ int launch_as(const bf16_params& p, hipStream_t stream) {
     const int64_t persistent = (int64_t)(n_cu / 8) * 8;
     if (grid > persistent) grid = persistent;
   }
-  hipLaunchKernelGGL((pa_prefill_bf16_kernel<D, NW, NS, DENSE, CHAIN, VARLEN>), dim3((uint32_t)grid), dim3(64 * NW), lds, stream, p);
+  hipLaunchKernelGGL((pa_prefill_bf16_kernel<D, NW, NS, DENSE, CHAIN, VARLEN, PAGED>), dim3((uint32_t)grid), dim3(64 * NW), lds, stream, p);
   return pa_note_hip(hipGetLastError());
 }
 
 template <int D, int NW, int NS>
 int launch(const bf16_params& p, hipStream_t stream) {
+  if (p.block_table) return launch_as<D, NW, NS, false, true, false, true>(p, stream);
   if (p.seq_len) {
     if (p.dense) return launch_as<D, NW, NS, true, true, true>(p, stream);
     return p.chain ? launch_as<D, NW, NS, false, true, true>(p, stream) : launch_as<D, NW, NS, false, false, true>(p, stream);
@@ -902,6 +949,7 @@ int pa_launch_prefill_bf16(const pa_prefill_args& a) {
   p.q_start = a.q_start; p.q_rows = a.q_rows > 0 ? a.q_rows : a.seq_len - a.q_start; p.kv_rows = a.kv_rows; p.i0 = (int32_t)(a.q_start / a.pat.block);
   p.c2 = a.scale * 1.44269504088896340736f;
   p.seq_len = a.seq_len_dev;
+  p.block_table = a.block_table; p.table_stride = a.table_stride; p.n_pages = (int32_t)a.n_pages;
   const int64_t tasks = (int64_t)p.G * p.B / QW;
   if (tasks > (1 << 20)) return POWATTN_UNSUPPORTED;
   p.tasks = (int32_t)tasks;
@@ -913,6 +961,12 @@ int pa_launch_prefill_bf16(const pa_prefill_args& a) {
   p.per_xcd = (int32_t)per_xcd;
   // chaining keeps the list row of the item after next in 63 lanes and two tile tables in LDS
   p.chain = (p.dense || (a.max_k <= 63 && (int64_t)a.max_k * p.subs <= TILE_CAP / 2)) ? 1 : 0;
+  if (a.block_table) {
+    // paged: explicit lists whose tile table fits twice over (key positions and pool rows), one length for the batch,
+    // pool rows in 32 bits
+    if (p.dense || a.seq_len_dev || a.max_k > 63 || (int64_t)a.max_k * p.subs > TILE_CAP / 4) return POWATTN_UNSUPPORTED;
+    if (a.n_pages < 1 || a.table_stride < 1 || a.n_pages * (int64_t)a.hkv * p.B > 0x7fffffffLL) return POWATTN_UNSUPPORTED;
+  }
 
   // ring of 4 stages: 128 KB of LDS at head_dim 128, 64 KB at head_dim 64
   if (a.head_dim == 128) return nw == 8 ? launch<128, 8, 4>(p, a.stream) : launch<128, 4, 4>(p, a.stream);

@@ -142,6 +142,37 @@ def test_prefill_chunk_argument_errors(L):
     assert _chunk(L, pat=pa.Pattern(64, 1, 0, flags=pa.DENSE), cnt=None, idx=None, max_k=0, q=None) == pa.INVALID_ARG
 
 
+def _chunk_paged(L, pat=None, cnt=FAKE, idx=FAKE, max_k=13, q=FAKE, k=FAKE, v=FAKE, table=FAKE, stride=64, n_pages=100,
+                 o=FAKE, lse=None, batch=1, hq=4, hkv=2, q_start=1024, q_len=512, d=128, dtype=pa.BF16, scale=0.0):
+    cp = (pat or pa.Pattern(64, 4, 1)).c()
+    return L.powattn_prefill_chunk_paged(ctypes.byref(cp), cnt, idx, max_k, q, k, v, table, stride, n_pages, o, lse,
+                                         batch, hq, hkv, q_start, q_len, d, dtype, scale, None)
+
+
+def test_prefill_chunk_paged_argument_errors(L):
+    # every case is refused on the host, before any launch
+    assert _chunk_paged(L, q=None) == pa.INVALID_ARG
+    assert _chunk_paged(L, k=None) == pa.INVALID_ARG
+    assert _chunk_paged(L, v=None) == pa.INVALID_ARG
+    assert _chunk_paged(L, o=None) == pa.INVALID_ARG
+    assert _chunk_paged(L, table=None) == pa.INVALID_ARG
+    assert _chunk_paged(L, cnt=None) == pa.INVALID_ARG
+    assert _chunk_paged(L, max_k=0) == pa.INVALID_ARG
+    assert _chunk_paged(L, stride=0) == pa.INVALID_ARG
+    assert _chunk_paged(L, n_pages=0) == pa.INVALID_ARG
+    assert _chunk_paged(L, hq=6, hkv=4) == pa.INVALID_ARG
+    assert _chunk_paged(L, q_start=-1) == pa.INVALID_ARG
+    assert _chunk_paged(L, q_len=0) == pa.INVALID_ARG
+    assert _chunk_paged(L, q_start=4000, q_len=128) == pa.INVALID_ARG         # runs past the table (64 blocks of 64)
+    assert _chunk_paged(L, scale=float("nan")) == pa.INVALID_ARG
+    assert _chunk_paged(L, dtype=pa.F32) == pa.UNSUPPORTED
+    assert _chunk_paged(L, d=96) == pa.UNSUPPORTED
+    assert _chunk_paged(L, pat=pa.Pattern(48, 4, 1), q_start=960) == pa.UNSUPPORTED
+    assert _chunk_paged(L, pat=pa.Pattern(64, 1, 0, flags=pa.DENSE)) == pa.UNSUPPORTED
+    assert _chunk_paged(L, max_k=64) == pa.UNSUPPORTED                         # list rows of at most 63 entries
+    assert _chunk_paged(L, n_pages=2 ** 31) == pa.UNSUPPORTED                  # pool rows are kept in 32 bits
+
+
 def test_prefill_varlen_argument_errors(L):
     cp = pa.Pattern(64, 4, 1).c()
 
