@@ -13,6 +13,7 @@ from test_gpu_backward import run_backward
 from test_gpu_decode import run_decode
 from test_gpu_decode_paged import test_paged_matches_oracle_and_contiguous as check_paged
 from test_gpu_prefill_chunk import test_chunks_equal_whole_prefill as check_chunks
+from test_gpu_prefill_chunk_paged import test_paged_chunks_equal_whole_prefill as check_paged_chunks
 from test_gpu_prefill_varlen import test_padded_batch as check_padded_batch
 
 pytestmark = pytest.mark.gpu
@@ -120,3 +121,39 @@ SERVING_CASES = draw_serving_cases(20250304, 24)
 def test_random_serving_shape(kind, args):
     print(kind, args, flush=True)
     {"chunk": check_chunks, "varlen": check_padded_batch, "paged": check_paged}[kind](*args)
+
+
+def draw_unaligned_chunk_cases(seed, count):
+    """Chunks cut at any token, against a contiguous cache and against a paged one."""
+    rng = random.Random(seed)
+    cases = []
+    for c in range(count):
+        kind = rng.choice(["chunk", "chunk_paged", "chunk_paged"])
+        hkv = rng.choice([1, 2, 4])
+        hq = hkv * rng.choice([1, 2, 4, 7])
+        d = rng.choice([64, 128])
+        W = rng.choice([0, 1, 2, 4, 5])
+        S = rng.choice([0, 1, 2])
+        B = rng.choice([64, 64, 128, 192, 256])
+        flags = rng.choice([pa.POWER, pa.POWER, 0]) if kind == "chunk_paged" else rng.choice([pa.POWER, 0, pa.DENSE])
+        if not (flags & (pa.POWER | pa.DENSE)) and W < 1:
+            W = 1
+        n = rng.randint(1, 2400)
+        cuts = [0] + sorted(set(rng.randint(1, n) for _ in range(rng.randint(0, 3))) - {n}) + [n]
+        batch = rng.choice([1, 2])
+        if hq * batch * n > 30000:
+            hq, hkv = 4, 2
+        if kind == "chunk":
+            cases.append((kind, (n, B, W, S, hq, hkv, d, batch, n + rng.randint(0, 300), cuts, flags)))
+        else:
+            cases.append((kind, (n, B, W, S, hq, hkv, d, batch, cuts, flags)))
+    return cases
+
+
+UNALIGNED_CASES = draw_unaligned_chunk_cases(20250305, 16)
+
+
+@pytest.mark.parametrize("kind,args", UNALIGNED_CASES, ids=[f"{i}-{k}" for i, (k, _) in enumerate(UNALIGNED_CASES)])
+def test_random_unaligned_chunks(kind, args):
+    print(kind, args, flush=True)
+    {"chunk": check_chunks, "chunk_paged": check_paged_chunks}[kind](*args)
