@@ -471,6 +471,45 @@ def main():
                          "bit_identical_to_contiguous": bool(torch.equal(o_pg, og) and torch.equal(lse_pg, lseg))}
         del kp, vp, o_pg, lse_pg
 
+    # ---------------- a serving step's prefill work in one launch (powattn_prefill_batch_paged): 32 sequences, each
+    # with its own context so far (0..60K tokens, any offset inside a block) and its own piece of 256..2048 new
+    # rows, K/V in one shuffled page pool; configuration 2's heads and pattern ----------------
+    batch_paged = None
+    if not args.no_dense:
+        Bp = dict(batch=32, hq=32, hkv=8, q_rows=2048, d=128, B=64, W=4, S=1, max_ctx=65536)
+        pat_b = pa.Pattern(Bp["B"], Bp["W"], Bp["S"])
+        rng_p = np.random.default_rng(7000)
+        st_np = rng_p.integers(0, Bp["max_ctx"] - Bp["q_rows"], Bp["batch"]).astype(np.int32)
+        ln_np = rng_p.integers(256, Bp["q_rows"] + 1, Bp["batch"]).astype(np.int32)
+        stride_b = Bp["max_ctx"] // Bp["B"]
+        used = (st_np.astype(np.int64) + ln_np + Bp["B"] - 1) // Bp["B"]
+        n_pages_b = int(used.sum()) + 64
+        perm_b = rng_p.permutation(n_pages_b)
+        table_np = np.zeros((Bp["batch"], stride_b), dtype=np.int32)
+        at = 0
+        for bi in range(Bp["batch"]):
+            table_np[bi, :used[bi]] = perm_b[at:at + used[bi]]
+            at += int(used[bi])
+        gb = torch.Generator(device=dev)
+        gb.manual_seed(7001)
+        kp_b = torch.randn(n_pages_b, Bp["hkv"], Bp["B"], Bp["d"], device=dev, dtype=torch.bfloat16, generator=gb)
+        vp_b = torch.randn(n_pages_b, Bp["hkv"], Bp["B"], Bp["d"], device=dev, dtype=torch.bfloat16, generator=gb)
+        q_b = torch.randn(Bp["batch"], Bp["hq"], Bp["q_rows"], Bp["d"], device=dev, dtype=torch.bfloat16, generator=gb)
+        o_b = torch.empty_like(q_b)
+        tab_b, st_b, ln_b = torch.from_numpy(table_np).to(dev), torch.from_numpy(st_np).to(dev), torch.from_numpy(ln_np).to(dev)
+        c_b, i_b, _ = pa.mask_build(pat_b, Bp["max_ctx"])
+        ms_b = stats(time_launches(lambda s: pa.prefill_batch_paged(pat_b, c_b, i_b, q_b, kp_b, vp_b, tab_b, st_b, ln_b, o=o_b,
+                                                                    want_lse=False), 20, 5))
+        csum_b = np.concatenate([[0], np.cumsum(c_b.cpu().numpy().astype(np.int64))])
+        pairs_b = int(sum(csum_b[(int(a) + int(n) - 1) // Bp["B"] + 1] - csum_b[int(a) // Bp["B"]] for a, n in zip(st_np, ln_np)))
+        f_b = flops_block(Bp["B"], Bp["d"], Bp["hq"], 1, pairs_b)
+        batch_paged = {"workload": "32 sequences, contexts so far 0..63K tokens (seeded uniform, any offset), pieces of 256..2048 new "
+                                   "rows padded to 2048, 32q/8kv heads, D=128, block 64, W=4, S=1, bf16; K/V in a shuffled pool of "
+                                   "%d pages; one launch, starts and lengths read on the device" % n_pages_b,
+                       "new_tokens": int(ln_np.sum()), "attended_block_pairs_whole_blocks": pairs_b, "kernel_ms": ms_b,
+                       "tflops": round(f_b / (ms_b["mean"] * 1e-3) / 1e12, 1)}
+        del kp_b, vp_b, q_b, o_b
+
     # ---------------- a serving batch of prompts of different lengths in one launch (powattn_prefill_varlen,
     # lengths in device memory): 64 prompts of 512..8192 tokens, configuration 2's heads and pattern ----------------
     varlen = None
@@ -680,6 +719,7 @@ def main():
         "layer_stack": stack,
         "prefill_varlen_batch": varlen,
         "prefill_paged_cache": paged_prefill,
+        "prefill_batch_paged": batch_paged,
         "backward_128k": backward,
         "prefill_sustained": sustained,
         "parity": parity,

@@ -191,6 +191,38 @@ int powattn_prefill_chunk_paged(const powattn_pattern* pattern,
                                 int32_t head_dim, int32_t dtype, float softmax_scale, void* hip_stream);
 
 /*
+ * A serving step's prefill work in one launch: for every sequence of the batch a
+ * piece of its prompt (its own start and its own number of rows) against the
+ * paged KV cache of powattn_prefill_chunk_paged.  Sequence b's rows are the
+ * positions d_q_start[b] .. d_q_start[b]+d_q_len[b]-1; the result is, bit for
+ * bit, that of powattn_prefill_chunk_paged called for each sequence alone
+ * (Equation 1 over the blocks of Algorithm 1; Section 4.3 for the setting).
+ *   q, o              device [batch, n_q_heads, q_rows, head_dim]: row r of sequence b is
+ *                     position d_q_start[b] + r; rows r >= d_q_len[b] are neither read nor written
+ *   lse               device [batch, n_q_heads, q_rows] fp32, or null
+ *   d_q_start         device int32 [batch], >= 0 (clamped into [0, table_stride*block])
+ *   d_q_len           device int32 [batch], 0 <= d_q_len[b] <= q_rows (clamped so that the context
+ *                     d_q_start[b] + d_q_len[b] stays inside the table); 0: the sequence is skipped
+ *   q_rows            rows per (sequence, head) slab of q/o/lse, 1 <= q_rows <= table_stride*block
+ *   k_pages, v_pages, d_block_table, table_stride, n_pages   as for powattn_prefill_chunk_paged;
+ *                     positions 0 .. d_q_start[b]+d_q_len[b]-1 of sequence b must be filled in
+ *   d_kv_cnt, d_kv_idx, max_k   the block lists, built for at least table_stride*block tokens
+ *                     (or for the longest context of the batch)
+ * Limits as for powattn_prefill_chunk_paged.  The lengths are read by the kernel: no
+ * host synchronisation, one launch whatever the mix of lengths; work is dealt by
+ * position in the padded batch, so q_rows should not be much larger than the longest piece.
+ * Errors: INVALID_ARG, UNSUPPORTED, HIP_ERROR.
+ */
+int powattn_prefill_batch_paged(const powattn_pattern* pattern,
+                                const int32_t* d_kv_cnt, const int32_t* d_kv_idx, int32_t max_k,
+                                const void* q, const void* k_pages, const void* v_pages,
+                                const int32_t* d_block_table, int32_t table_stride, int64_t n_pages,
+                                const int32_t* d_q_start, const int32_t* d_q_len, int64_t q_rows,
+                                void* o, float* lse,
+                                int32_t batch, int32_t n_q_heads, int32_t n_kv_heads,
+                                int32_t head_dim, int32_t dtype, float softmax_scale, void* hip_stream);
+
+/*
  * powattn_prefill for a batch of sequences of different lengths (what a serving
  * batch of prompts looks like; Section 4.3 measures end-to-end generation), in
  * ONE launch, with the lengths in device memory (no host copy, no

@@ -23,7 +23,7 @@ BF16, F32 = 0, 1
 EXPORTS = (
     "powattn_version", "powattn_strerror", "powattn_num_blocks", "powattn_max_k",
     "powattn_row_host", "powattn_mask_build", "powattn_prefill",
-    "powattn_prefill_chunk", "powattn_prefill_chunk_paged", "powattn_prefill_varlen", "powattn_decode_workspace_bytes", "powattn_decode",
+    "powattn_prefill_chunk", "powattn_prefill_chunk_paged", "powattn_prefill_batch_paged", "powattn_prefill_varlen", "powattn_decode_workspace_bytes", "powattn_decode",
     "powattn_decode_static", "powattn_decode_paged", "powattn_backward_workspace_bytes", "powattn_backward",
 )
 
@@ -84,6 +84,9 @@ def lib() -> ctypes.CDLL:
     L.powattn_prefill_chunk.argtypes = [P, vp, vp, i32, vp, vp, vp, vp, vp, i32, i32, i32, i64, i64, i64, i32, i32, f32, vp]
     L.powattn_prefill_chunk_paged.restype = ctypes.c_int
     L.powattn_prefill_chunk_paged.argtypes = [P, vp, vp, i32, vp, vp, vp, vp, i32, i64, vp, vp, i32, i32, i32, i64, i64,
+                                              i32, i32, f32, vp]
+    L.powattn_prefill_batch_paged.restype = ctypes.c_int
+    L.powattn_prefill_batch_paged.argtypes = [P, vp, vp, i32, vp, vp, vp, vp, i32, i64, vp, vp, i64, vp, vp, i32, i32, i32,
                                               i32, i32, f32, vp]
     L.powattn_prefill_varlen.restype = ctypes.c_int
     L.powattn_prefill_varlen.argtypes = [P, vp, vp, i32, vp, vp, vp, vp, vp, i32, i32, i32, vp, i64,
@@ -282,6 +285,43 @@ def prefill_chunk_paged(pattern: Pattern, kv_cnt, kv_idx, q, k_pages, v_pages, b
                                            batch, hq, hkv, int(q_start), q_len, d, _dtype_code(q),
                                            float(softmax_scale), _stream(stream))
     _check(st, "powattn_prefill_chunk_paged")
+    return o, lse
+
+
+def prefill_batch_paged(pattern: Pattern, kv_cnt, kv_idx, q, k_pages, v_pages, block_table, q_start, q_len, o=None,
+                        lse=None, softmax_scale=0.0, want_lse=True, stream=None):
+    """powattn_prefill_batch_paged.  q/o: [b,Hq,q_rows,D]; pages: [n_pages,Hkv,block,D]; block_table int32
+    [b, table_stride]; q_start, q_len int32 [b] on the device.  Returns (o, lse); rows at or beyond a sequence's
+    q_len are left as they were."""
+    batch, hq, q_rows, d = q.shape
+    n_pages, hkv, blk = k_pages.shape[0], k_pages.shape[1], k_pages.shape[2]
+    if k_pages.shape != (n_pages, hkv, blk, d) or v_pages.shape != k_pages.shape:
+        raise ValueError("page pool shape mismatch")
+    if blk != pattern.block:
+        raise ValueError("a page holds one block of the pattern")
+    if k_pages.dtype != q.dtype or v_pages.dtype != q.dtype:
+        raise ValueError("q/k/v dtype mismatch")
+    if block_table.dtype != torch.int32 or block_table.dim() != 2 or block_table.shape[0] != batch:
+        raise ValueError("block_table must be int32 [batch, table_stride]")
+    if not block_table.is_contiguous():
+        raise ValueError("block_table must be contiguous")
+    for t in (q_start, q_len):
+        if t.dtype != torch.int32 or t.shape != (batch,) or t.device != q.device:
+            raise ValueError("q_start and q_len must be int32 [batch] on the device of q")
+    if kv_idx is None or kv_cnt is None:
+        raise ValueError("the paged form needs block lists")
+    if kv_cnt.shape[0] < block_table.shape[1]:
+        raise ValueError("block lists shorter than the longest context the block table can describe")
+    if o is None:
+        o = torch.empty_like(q)
+    if lse is None and want_lse:
+        lse = torch.empty((batch, hq, q_rows), dtype=torch.float32, device=q.device)
+    st = lib().powattn_prefill_batch_paged(ctypes.byref(pattern.c()), _ptr(kv_cnt), _ptr(kv_idx), kv_idx.shape[1],
+                                           _ptr(q), _ptr(k_pages), _ptr(v_pages), _ptr(block_table),
+                                           block_table.shape[1], n_pages, _ptr(q_start), _ptr(q_len), q_rows,
+                                           _ptr(o), _ptr(lse), batch, hq, hkv, d, _dtype_code(q),
+                                           float(softmax_scale), _stream(stream))
+    _check(st, "powattn_prefill_batch_paged")
     return o, lse
 
 

@@ -206,6 +206,47 @@ extern "C" int powattn_prefill_chunk_paged(const powattn_pattern* pattern,
   return pa_launch_prefill_bf16(a);
 }
 
+extern "C" int powattn_prefill_batch_paged(const powattn_pattern* pattern,
+                                           const int32_t* d_kv_cnt, const int32_t* d_kv_idx, int32_t max_k,
+                                           const void* q, const void* k_pages, const void* v_pages,
+                                           const int32_t* d_block_table, int32_t table_stride, int64_t n_pages,
+                                           const int32_t* d_q_start, const int32_t* d_q_len, int64_t q_rows,
+                                           void* o, float* lse,
+                                           int32_t batch, int32_t n_q_heads, int32_t n_kv_heads,
+                                           int32_t head_dim, int32_t dtype, float softmax_scale, void* hip_stream) {
+  int st = pa_check_pattern(pattern);
+  if (st != POWATTN_OK) return st;
+  if (!q || !k_pages || !v_pages || !o || !d_block_table || !d_q_start || !d_q_len) return POWATTN_INVALID_ARG;
+  if (batch < 1 || n_q_heads < 1 || n_kv_heads < 1 || head_dim < 1) return POWATTN_INVALID_ARG;
+  if (table_stride < 1 || n_pages < 1 || q_rows < 1) return POWATTN_INVALID_ARG;
+  if (n_q_heads % n_kv_heads != 0) return POWATTN_INVALID_ARG;
+  if (!d_kv_cnt || !d_kv_idx || max_k < 1) return POWATTN_INVALID_ARG;
+  const int64_t max_ctx = (int64_t)table_stride * pattern->block;      // the longest context the tables can describe
+  if (q_rows > max_ctx) return POWATTN_INVALID_ARG;
+  if (powattn_num_blocks(pattern, max_ctx) < 0) return POWATTN_INVALID_ARG;
+  if (!(softmax_scale == softmax_scale)) return POWATTN_INVALID_ARG;  // NaN
+  if (pattern->flags & POWATTN_DENSE) return POWATTN_UNSUPPORTED;
+  if (dtype != POWATTN_BF16) return POWATTN_UNSUPPORTED;
+  if (!supported_head_dim(head_dim)) return POWATTN_UNSUPPORTED;
+  if ((int64_t)batch * n_q_heads > 65535 * 16) return POWATTN_UNSUPPORTED;
+  if (pattern->block % 64 != 0 || pattern->block > 1024) return POWATTN_UNSUPPORTED;
+
+  pa_prefill_args a;
+  a.pat = *pattern;
+  a.kv_cnt = d_kv_cnt; a.kv_idx = d_kv_idx; a.max_k = max_k;
+  a.q = q; a.k = k_pages; a.v = v_pages; a.o = o; a.lse = lse;
+  a.batch = batch; a.hq = n_q_heads; a.hkv = n_kv_heads;
+  a.seq_len = max_ctx; a.q_start = 0; a.kv_rows = 0; a.q_rows = q_rows;
+  a.seq_len_dev = d_q_len; a.q_start_dev = d_q_start;
+  a.block_table = d_block_table; a.table_stride = table_stride; a.n_pages = n_pages;
+  // query blocks a piece of q_rows rows can touch when it starts anywhere inside a block
+  a.nb = (int32_t)((q_rows + pattern->block - 2) / pattern->block + 1);
+  a.head_dim = head_dim;
+  a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)head_dim);
+  a.stream = (hipStream_t)hip_stream;
+  return pa_launch_prefill_bf16(a);
+}
+
 extern "C" int powattn_prefill_varlen(const powattn_pattern* pattern,
                                       const int32_t* d_kv_cnt, const int32_t* d_kv_idx, int32_t max_k,
                                       const void* q, const void* k, const void* v, void* o, float* lse,

@@ -5,7 +5,7 @@
 #include "../../include/powattn.h"
 #include "pattern.h"
 
-#define POWATTN_VERSION_NUMBER 105  // 0.1.5; moves with every change to a kernel (bench.py ties its profiled traffic figures to it)
+#define POWATTN_VERSION_NUMBER 106  // 0.1.6; moves with every change to a kernel (bench.py ties its profiled traffic figures to it)
 
 // Records a HIP error for powattn_strerror and maps it to a status.
 int pa_note_hip(hipError_t e);
@@ -33,6 +33,8 @@ struct pa_prefill_args {
   int32_t nb;      // query blocks: ceil((seq_len - q_start) / block)
   const int32_t* seq_len_dev;   // device [batch]: every sequence's own length, seq_len then being the padded one; or null
   // paged KV cache (k, v are then page pools [n_pages, hkv, block, head_dim]); null: contiguous slabs of kv_rows rows
+  const int32_t* q_start_dev = nullptr;   // with seq_len_dev: device [batch], every sequence's first query position
+                                          // (seq_len_dev[b] then counts its query rows); null: 0 for all
   const int32_t* block_table = nullptr;   // device [batch, table_stride]: page of every block of every sequence
   int32_t table_stride = 0;
   int64_t n_pages = 0;

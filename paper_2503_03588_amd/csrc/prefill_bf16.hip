@@ -75,7 +75,7 @@ constexpr float RESCALE_TAU = 8.0f;   // running max is only raised when exceede
 struct bf16_params {
   const __bf16* q; const __bf16* k; const __bf16* v; __bf16* o; float* lse;
   const int32_t* kv_cnt; const int32_t* kv_idx;
-  int32_t max_k, nb, B, hq, hkv, G, dense;
+  int32_t max_k, nb, B, hq, hkv, G, dense, batch;
   int32_t subs;      // 64-key tiles per block
   int32_t tasks;     // G * B / 32
   int32_t chunks;    // workgroups per (batch, kv head, query block)
@@ -89,6 +89,8 @@ struct bf16_params {
   int32_t i0;        // first query block: q_start / B
   float c2;          // softmax scale * log2(e)
   const int32_t* seq_len;   // padded batch of sequences of different lengths: device array [batch]; N is then the padded length
+  const int32_t* q_start_dev;   // with seq_len: every sequence's own first query position, device array [batch] (seq_len[b]
+                                // is then the number of its query rows); null: all sequences start at 0
   const int32_t* block_table;   // paged cache: device [batch, table_stride], page of every block; k, v are the page pools
   int32_t table_stride, n_pages;
 };
@@ -184,17 +186,28 @@ void pa_prefill_bf16_kernel(bf16_params p) {
   constexpr bool chained = CHAIN;      // tables in halves, list rows prefetched
   constexpr int tab_half = CHAIN ? (PAGED ? TILE_CAP / 4 : TILE_CAP / 2) : 0;
   constexpr int PHYS = TILE_CAP / 2;   // paged: entry e's first pool row sits at s_tile[PHYS + e]
-  static_assert(!PAGED || (CHAIN && !DENSE && !VARLEN), "paged caches: explicit lists, chained items");
+  static_assert(!PAGED || (CHAIN && !DENSE), "paged caches: explicit lists, chained items");
 
   // Items are numbered L = ((b*hkv + kvh)*nb + r)*chunks + chunk with r counting query blocks from the last one
-  // down (longest rows first, which matters for the dense list).  The first item is decoded by division, the
+  // down (longest rows first, which matters for the dense list); with sequences of different lengths
+  // L = ((kvh*batch + b)*nb + r)*chunks + chunk, so that the contiguous share of an XCD spans all sequences (one KV
+  // head each when there are eight) and the XCDs finish together whatever the mix of lengths.  The first item is decoded by division, the
   // following ones by adding the stride nslots digit by digit with carries: all scalar, no division in the loop.
-  struct item_t { int chunk, r, kvh, b, i, subs_diag, n; };   // n: keys (= tokens) of the item's sequence
+  struct item_t { int chunk, r, kvh, b, i, subs_diag, n, qs; };   // n: keys (= tokens) of the item's sequence; qs: its first query
   auto finish_item = [&](item_t& it) {
     it.i = p.i0 + p.nb - 1 - it.r;
-    if (VARLEN) {                      // uniform over the workgroup: a scalar load; lengths outside [0, N] are clamped
+    if (VARLEN) {                      // uniform over the workgroup: scalar loads; values outside [0, N] are clamped
+      int qs = 0;
+      if (p.q_start_dev) {
+        qs = p.q_start_dev[it.b];
+        qs = qs < 0 ? 0 : (qs > (int)p.N ? (int)p.N : qs);
+        it.i += qs / p.B;              // the launch numbers a sequence's query blocks from its own first one
+      }
       const int n = p.seq_len[it.b];
-      it.n = n < 0 ? 0 : (n > (int)p.N ? (int)p.N : n);
+      it.qs = qs;
+      int room = (int)p.N - qs;        // rows that fit the context, and the slab of Q/O
+      if ((int64_t)room > p.q_rows) room = (int)p.q_rows;
+      it.n = qs + (n < 0 ? 0 : (n > room ? room : n));
     }
     // tiles of the diagonal block needed by any wavefront of the item
     int last_task = it.chunk * NW + NW - 1;
@@ -206,18 +219,29 @@ void pa_prefill_bf16_kernel(bf16_params p) {
     item_t it;
     it.chunk = (int)(L % (uint32_t)p.chunks); L /= (uint32_t)p.chunks;
     it.r = (int)(L % (uint32_t)p.nb); L /= (uint32_t)p.nb;
-    it.kvh = (int)(L % (uint32_t)p.hkv);
-    it.b = (int)(L / (uint32_t)p.hkv);
-    it.i = 0; it.subs_diag = 0; it.n = 0;
+    if (VARLEN) {                      // the KV head is the slowest digit: an XCD's share then holds every sequence
+      it.b = (int)(L % (uint32_t)p.batch);
+      it.kvh = (int)(L / (uint32_t)p.batch);
+    } else {
+      it.kvh = (int)(L % (uint32_t)p.hkv);
+      it.b = (int)(L / (uint32_t)p.hkv);
+    }
+    it.i = 0; it.subs_diag = 0; it.n = 0; it.qs = 0;
     return it;
   };
   const item_t stride = digits((uint32_t)nslots);
   auto next_item = [&](const item_t& cur) -> item_t {
     item_t it = cur;
     it.chunk += stride.chunk; if (it.chunk >= p.chunks) { it.chunk -= p.chunks; ++it.r; }
-    it.r += stride.r;         if (it.r >= p.nb) { it.r -= p.nb; ++it.kvh; }
-    it.kvh += stride.kvh;     if (it.kvh >= p.hkv) { it.kvh -= p.hkv; ++it.b; }
-    it.b += stride.b;
+    if (VARLEN) {
+      it.r += stride.r;       if (it.r >= p.nb) { it.r -= p.nb; ++it.b; }
+      it.b += stride.b;       if (it.b >= p.batch) { it.b -= p.batch; ++it.kvh; }
+      it.kvh += stride.kvh;
+    } else {
+      it.r += stride.r;       if (it.r >= p.nb) { it.r -= p.nb; ++it.kvh; }
+      it.kvh += stride.kvh;   if (it.kvh >= p.hkv) { it.kvh -= p.hkv; ++it.b; }
+      it.b += stride.b;
+    }
     finish_item(it);
     return it;
   };
@@ -228,7 +252,9 @@ void pa_prefill_bf16_kernel(bf16_params p) {
   int n_items = n_raw, raw2 = 0;
   // keys of an item's sequence (one value for the whole launch unless the sequences have lengths of their own)
   auto keys_of = [&](const item_t& x) -> int { return VARLEN ? x.n : (int)p.N; };
-  auto exists = [&](const item_t& x) -> bool { return !VARLEN || (int64_t)x.i * p.B < x.n; };
+  auto exists = [&](const item_t& x) -> bool { return !VARLEN || (x.n > x.qs && (int64_t)x.i * p.B < x.n); };
+  // position of the first row of Q/O
+  auto qs_of = [&](const item_t& x) -> int64_t { return VARLEN ? (int64_t)x.qs : p.q_start; };
   auto next_valid = [&](const item_t& cur, int& raw) -> item_t {
     item_t x = cur;
     while (raw + 1 < n_raw) {
@@ -438,12 +464,12 @@ void pa_prefill_bf16_kernel(bf16_params p) {
     const bool act = task < p.tasks;
     const int g = act ? task / slices : 0, sl = act ? task % slices : 0;
     const int64_t tok0 = (int64_t)it.i * p.B + sl * QW + (ln & ~3);          // first row of this lane's quad
-    const __bf16* qbase = p.q + (((int64_t)it.b * p.hq + it.kvh * p.G + g) * p.q_rows + (tok0 - p.q_start)) * D
+    const __bf16* qbase = p.q + (((int64_t)it.b * p.hq + it.kvh * p.G + g) * p.q_rows + (tok0 - qs_of(it))) * D
                           + (D / 2) * hh + 8 * (lane & 3);
 #pragma unroll
     for (int m = 0; m < NC; ++m) {
       const int rho = m / QE, e = m % QE;
-      const bool ok = act && tok0 + rho < keys_of(it) && tok0 + rho >= p.q_start;   // (a chunk may start inside a block)
+      const bool ok = act && tok0 + rho < keys_of(it) && tok0 + rho >= qs_of(it);   // (a chunk may start inside a block)
       qraw[m] = ok ? *reinterpret_cast<const u32x4*>(qbase + (int64_t)rho * D + 32 * e) : u32x4{0, 0, 0, 0};
     }
   };
@@ -866,7 +892,7 @@ void pa_prefill_bf16_kernel(bf16_params p) {
       for (int c = 0; c < NC; ++c) asm volatile("" : "+v"(qraw[c]));
       const int li = lane & 3;
       const int64_t tok0 = tok - li;                   // first row of the quad
-      __bf16* obase = p.o + (((int64_t)it.b * p.hq + h) * p.q_rows + (tok0 - p.q_start)) * D + hh * (D / 2) + 8 * li;
+      __bf16* obase = p.o + (((int64_t)it.b * p.hq + h) * p.q_rows + (tok0 - qs_of(it))) * D + hh * (D / 2) + 8 * li;
 #pragma unroll
       for (int u = 0; u < NP / 8; ++u) {
         uint32_t c[4][4];                              // c[m][word]: chunk 4u+m of this lane's row
@@ -890,12 +916,12 @@ void pa_prefill_bf16_kernel(bf16_params p) {
 #pragma unroll
         for (int k2 = 0; k2 < 4; ++k2) {
           const u32x4 wv = {c[k2][0], c[k2][1], c[k2][2], c[k2][3]};
-          if (active && tok0 + k2 < keys_of(it) && tok0 + k2 >= p.q_start)
+          if (active && tok0 + k2 < keys_of(it) && tok0 + k2 >= qs_of(it))
             *reinterpret_cast<u32x4*>(obase + (int64_t)k2 * D + 32 * u) = wv;
         }
       }
-      if (active && tok < keys_of(it) && tok >= p.q_start && p.lse && hh == 0)
-        p.lse[((int64_t)it.b * p.hq + h) * p.q_rows + (tok - p.q_start)] = (m_run + log2f(ltot)) * 0.69314718055994530942f;
+      if (active && tok < keys_of(it) && tok >= qs_of(it) && p.lse && hh == 0)
+        p.lse[((int64_t)it.b * p.hq + h) * p.q_rows + (tok - qs_of(it))] = (m_run + log2f(ltot)) * 0.69314718055994530942f;
     }
     it = it1; it1 = it2; it2 = VARLEN ? next_valid(it2, raw2) : next_item(it2);
   }
@@ -925,7 +951,7 @@ int launch_as(const bf16_params& p, hipStream_t stream) {
 
 template <int D, int NW, int NS>
 int launch(const bf16_params& p, hipStream_t stream) {
-  if (p.block_table) return launch_as<D, NW, NS, false, true, false, true>(p, stream);
+  if (p.block_table) return p.seq_len ? launch_as<D, NW, NS, false, true, true, true>(p, stream) : launch_as<D, NW, NS, false, true, false, true>(p, stream);
   if (p.seq_len) {
     if (p.dense) return launch_as<D, NW, NS, true, true, true>(p, stream);
     return p.chain ? launch_as<D, NW, NS, false, true, true>(p, stream) : launch_as<D, NW, NS, false, false, true>(p, stream);
@@ -941,30 +967,33 @@ int pa_launch_prefill_bf16(const pa_prefill_args& a) {
   bf16_params p;
   p.q = (const __bf16*)a.q; p.k = (const __bf16*)a.k; p.v = (const __bf16*)a.v; p.o = (__bf16*)a.o; p.lse = a.lse;
   p.kv_cnt = a.kv_cnt; p.kv_idx = a.kv_idx; p.max_k = a.max_k; p.nb = a.nb; p.B = a.pat.block;
-  p.hq = a.hq; p.hkv = a.hkv; p.G = a.hq / a.hkv; p.dense = (a.pat.flags & POWATTN_DENSE) ? 1 : 0;
+  p.hq = a.hq; p.hkv = a.hkv; p.batch = a.batch; p.G = a.hq / a.hkv; p.dense = (a.pat.flags & POWATTN_DENSE) ? 1 : 0;
   p.subs = p.B / KT;
   if (!p.dense && (int64_t)a.max_k * p.subs > TILE_CAP) return POWATTN_UNSUPPORTED;
   if (a.seq_len > 0x7fffffffLL - 1024) return POWATTN_UNSUPPORTED;   // key positions are kept in 32 bits
   p.N = a.seq_len;
   p.q_start = a.q_start; p.q_rows = a.q_rows > 0 ? a.q_rows : a.seq_len - a.q_start; p.kv_rows = a.kv_rows; p.i0 = (int32_t)(a.q_start / a.pat.block);
   p.c2 = a.scale * 1.44269504088896340736f;
-  p.seq_len = a.seq_len_dev;
+  p.seq_len = a.seq_len_dev; p.q_start_dev = a.q_start_dev;
   p.block_table = a.block_table; p.table_stride = a.table_stride; p.n_pages = (int32_t)a.n_pages;
   const int64_t tasks = (int64_t)p.G * p.B / QW;
   if (tasks > (1 << 20)) return POWATTN_UNSUPPORTED;
   p.tasks = (int32_t)tasks;
   const int nw = p.tasks > 4 ? 8 : 4;
   p.chunks = (p.tasks + nw - 1) / nw;
-  p.total_wg = (int64_t)a.batch * a.hkv * a.nb * p.chunks;
+  // Sequences of different lengths: an odd count of block numbers per sequence (the extra one lies behind every
+  // sequence and is passed over), so that the power-of-two stride of a workgroup's item numbers walks through all
+  // block positions instead of returning to the same few, whose rows exist for different shares of the batch.
+  if (a.seq_len_dev && (p.nb & 1) == 0) ++p.nb;
+  p.total_wg = (int64_t)a.batch * a.hkv * p.nb * p.chunks;
   const int64_t per_xcd = (p.total_wg + 7) / 8;
   if (per_xcd * 8 > 0x7fffffffLL) return POWATTN_UNSUPPORTED;
   p.per_xcd = (int32_t)per_xcd;
   // chaining keeps the list row of the item after next in 63 lanes and two tile tables in LDS
   p.chain = (p.dense || (a.max_k <= 63 && (int64_t)a.max_k * p.subs <= TILE_CAP / 2)) ? 1 : 0;
   if (a.block_table) {
-    // paged: explicit lists whose tile table fits twice over (key positions and pool rows), one length for the batch,
-    // pool rows in 32 bits
-    if (p.dense || a.seq_len_dev || a.max_k > 63 || (int64_t)a.max_k * p.subs > TILE_CAP / 4) return POWATTN_UNSUPPORTED;
+    // paged: explicit lists whose tile table fits twice over (key positions and pool rows), pool rows in 32 bits
+    if (p.dense || a.max_k > 63 || (int64_t)a.max_k * p.subs > TILE_CAP / 4) return POWATTN_UNSUPPORTED;
     if (a.n_pages < 1 || a.table_stride < 1 || a.n_pages * (int64_t)a.hkv * p.B > 0x7fffffffLL) return POWATTN_UNSUPPORTED;
   }
 

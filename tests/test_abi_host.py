@@ -173,6 +173,32 @@ def test_prefill_chunk_paged_argument_errors(L):
     assert _chunk_paged(L, n_pages=2 ** 31) == pa.UNSUPPORTED                  # pool rows are kept in 32 bits
 
 
+def _batch_paged(L, pat=None, cnt=FAKE, idx=FAKE, max_k=13, q=FAKE, k=FAKE, v=FAKE, table=FAKE, stride=64, n_pages=100,
+                 starts=FAKE, lens=FAKE, q_rows=512, o=FAKE, lse=None, batch=2, hq=4, hkv=2, d=128, dtype=pa.BF16, scale=0.0):
+    cp = (pat or pa.Pattern(64, 4, 1)).c()
+    return L.powattn_prefill_batch_paged(ctypes.byref(cp), cnt, idx, max_k, q, k, v, table, stride, n_pages, starts, lens,
+                                         q_rows, o, lse, batch, hq, hkv, d, dtype, scale, None)
+
+
+def test_prefill_batch_paged_argument_errors(L):
+    for name in ("q", "k", "v", "o", "table", "starts", "lens", "cnt", "idx"):
+        assert _batch_paged(L, **{name: None}) == pa.INVALID_ARG, name
+    assert _batch_paged(L, max_k=0) == pa.INVALID_ARG
+    assert _batch_paged(L, stride=0) == pa.INVALID_ARG
+    assert _batch_paged(L, n_pages=0) == pa.INVALID_ARG
+    assert _batch_paged(L, q_rows=0) == pa.INVALID_ARG
+    assert _batch_paged(L, q_rows=64 * 64 + 1) == pa.INVALID_ARG                # more rows than the table describes
+    assert _batch_paged(L, batch=0) == pa.INVALID_ARG
+    assert _batch_paged(L, hq=6, hkv=4) == pa.INVALID_ARG
+    assert _batch_paged(L, scale=float("nan")) == pa.INVALID_ARG
+    assert _batch_paged(L, dtype=pa.F32) == pa.UNSUPPORTED
+    assert _batch_paged(L, d=96) == pa.UNSUPPORTED
+    assert _batch_paged(L, pat=pa.Pattern(48, 4, 1)) == pa.UNSUPPORTED
+    assert _batch_paged(L, pat=pa.Pattern(64, 1, 0, flags=pa.DENSE)) == pa.UNSUPPORTED
+    assert _batch_paged(L, max_k=64) == pa.UNSUPPORTED
+    assert _batch_paged(L, n_pages=2 ** 31) == pa.UNSUPPORTED
+
+
 def test_prefill_varlen_argument_errors(L):
     cp = pa.Pattern(64, 4, 1).c()
 

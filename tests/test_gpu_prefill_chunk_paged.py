@@ -111,3 +111,112 @@ def test_prompt_in_paged_chunks_then_paged_decode():
         # a decode step and the prefill row round differently: both are within the bar of the oracle, hence 2x of each other
         assert (od.float() - o_ref[:, :, t].float()).abs().max().item() <= 2 * TOL_O["bf16"]
         assert (ld - l_ref[:, :, t]).abs().max().item() <= 2 * TOL_LSE
+
+
+def pool_for(k, v, ctx, block, n_extra, seed):
+    """One pool for a batch whose sequence b holds its first ctx[b] positions; returns pools and table [b, nbk]."""
+    b, hkv, n, d = k.shape
+    nbk = (n + block - 1) // block
+    used = [(c + block - 1) // block for c in ctx]
+    n_pages = sum(used) + n_extra
+    perm = np.random.default_rng(seed).permutation(n_pages)
+    table = np.full((b, nbk), -7, dtype=np.int32)
+    kp = torch.full((n_pages, hkv, block, d), float("nan"), dtype=k.dtype)
+    vp = torch.full((n_pages, hkv, block, d), float("nan"), dtype=v.dtype)
+    at = 0
+    for bi in range(b):
+        for j in range(used[bi]):
+            pg = int(perm[at]); at += 1
+            table[bi, j] = pg
+            lo, hi = j * block, min((j + 1) * block, ctx[bi])
+            kp[pg, :, : hi - lo] = k[bi, :, lo:hi]
+            vp[pg, :, : hi - lo] = v[bi, :, lo:hi]
+    return kp, vp, torch.from_numpy(table)
+
+
+@pytest.mark.parametrize("n,B,W,S,hq,hkv,d,pieces,q_rows,flags", [
+    # (q_start, q_len) per sequence
+    (3000, 64, 4, 1, 8, 2, 128, [(0, 700), (1024, 512), (2999, 1), (100, 0), (1500, 777)], 800, pa.POWER),
+    (2048, 128, 4, 1, 8, 2, 128, [(0, 2048), (1000, 1048), (2047, 1)], 2048, pa.POWER),       # whole prompts and a decode-like row
+    (2500, 64, 2, 0, 7, 1, 128, [(63, 130), (64, 64), (0, 1), (2400, 100)], 130, pa.POWER),    # GQA 7, no sink
+    (1900, 192, 3, 1, 4, 2, 64, [(191, 500), (192, 384), (5, 1000)], 1000, 0),                 # sliding window, pages of 192, head_dim 64
+    (1024, 256, 5, 1, 8, 2, 128, [(0, 0), (0, 0)], 16, pa.POWER),                              # nothing to do
+])
+def test_batch_of_pieces_equals_each_piece_alone(n, B, W, S, hq, hkv, d, pieces, q_rows, flags):
+    pat = pa.Pattern(B, W, S, flags)
+    batch = len(pieces)
+    q, k, v = synth.qkv(batch, hq, hkv, n, d, "bf16", seed=71)
+    ctx = [a + ln for a, ln in pieces]
+    kp, vp, table = pool_for(k, v, ctx, B, n_extra=4, seed=72)
+    kpg, vpg, tg = kp.cuda(), vp.cuda(), table.cuda()
+    cnt, idx, _ = pa.mask_build(pat, table.shape[1] * B)
+    qb = torch.full((batch, hq, q_rows, d), float("nan"), dtype=torch.bfloat16)          # padding rows must not be read
+    for bi, (a, ln) in enumerate(pieces):
+        qb[bi, :, :ln] = q[bi, :, a:a + ln]
+    sentinel = 12345.0
+    ob = torch.full((batch, hq, q_rows, d), sentinel, dtype=torch.bfloat16, device="cuda")
+    lb = torch.full((batch, hq, q_rows), sentinel, dtype=torch.float32, device="cuda")
+    starts = torch.tensor([a for a, _ in pieces], dtype=torch.int32).cuda()
+    lens = torch.tensor([ln for _, ln in pieces], dtype=torch.int32).cuda()
+    pa.prefill_batch_paged(pat, cnt, idx, qb.cuda(), kpg, vpg, tg, starts, lens, o=ob, lse=lb)
+    torch.cuda.synchronize()
+    for bi, (a, ln) in enumerate(pieces):
+        assert (ob[bi, :, ln:] == sentinel).all() and (lb[bi, :, ln:] == sentinel).all(), bi   # rows behind a piece untouched
+        if ln == 0:
+            continue
+        o1, l1 = pa.prefill_chunk_paged(pat, cnt, idx, q[bi:bi + 1, :, a:a + ln].contiguous().cuda(), kpg, vpg,
+                                        tg[bi:bi + 1].contiguous(), a)
+        torch.cuda.synchronize()
+        assert torch.isfinite(o1.float()).all()
+        assert torch.equal(ob[bi:bi + 1, :, :ln], o1), (bi, a, ln)
+        assert torch.equal(lb[bi:bi + 1, :, :ln], l1), (bi, a, ln)
+
+
+def test_batch_of_pieces_against_the_oracle():
+    pat = pa.Pattern(64, 4, 1)
+    n, hq, hkv, d = 2200, 8, 2, 128
+    pieces = [(0, 300), (1000, 300), (1900, 300)]
+    q, k, v = synth.qkv(3, hq, hkv, n, d, "bf16", seed=73)
+    kp, vp, table = pool_for(k, v, [a + ln for a, ln in pieces], 64, n_extra=1, seed=74)
+    cnt, idx, _ = pa.mask_build(pat, table.shape[1] * 64)
+    qb = torch.stack([q[bi, :, a:a + ln] for bi, (a, ln) in enumerate(pieces)])
+    o, l = pa.prefill_batch_paged(pat, cnt, idx, qb.cuda(), kp.cuda(), vp.cuda(), table.cuda(),
+                                  torch.tensor([a for a, _ in pieces], dtype=torch.int32).cuda(),
+                                  torch.tensor([ln for _, ln in pieces], dtype=torch.int32).cuda())
+    torch.cuda.synchronize()
+    for bi, (a, ln) in enumerate(pieces):
+        rows = [a, a + 63, a + 64, a + ln - 1]
+        oo, ol = orc.attention_rows(synth.to_numpy_storage(q[bi:bi + 1]), synth.to_numpy_storage(k[bi:bi + 1]),
+                                    synth.to_numpy_storage(v[bi:bi + 1]), rows, oracle_pattern(pat))
+        sel = [r - a for r in rows]
+        assert np.abs(o[bi:bi + 1].double().cpu().numpy()[:, :, sel] - oo).max() <= TOL_O["bf16"]
+        assert np.abs(l[bi:bi + 1].double().cpu().numpy()[:, :, sel] - ol).max() <= TOL_LSE
+
+
+def test_batch_lengths_out_of_range_are_clamped():
+    # a length beyond the slab of Q/O, a start beyond the table, a negative start, a length that runs past the table:
+    # clamped, finite, no stray access
+    pat = pa.Pattern(64, 4, 1)
+    n, hq, hkv, d, q_rows = 1024, 4, 2, 128, 200
+    q, k, v = synth.qkv(4, hq, hkv, n, d, "bf16", seed=75)
+    kp, vp, table = pool_for(k, v, [n, n, n, n], 64, n_extra=0, seed=76)
+    kpg, vpg, tg = kp.cuda(), vp.cuda(), table.cuda()
+    cnt, idx, _ = pa.mask_build(pat, n)
+    qb = q[:, :, :q_rows].contiguous()
+    qb[3, :, :24] = q[3, :, 1000:1024]
+    o = torch.zeros((4, hq, q_rows, d), dtype=torch.bfloat16, device="cuda")
+    starts = torch.tensor([0, 10 ** 9, -50, 1000], dtype=torch.int32).cuda()
+    lens = torch.tensor([10 ** 9, 200, 200, 10 ** 9], dtype=torch.int32).cuda()
+    pa.prefill_batch_paged(pat, cnt, idx, qb.cuda(), kpg, vpg, tg, starts, lens, o=o, want_lse=False)
+    torch.cuda.synchronize()
+    assert torch.isfinite(o.float()).all()
+    assert (o[1] == 0).all()                      # start clamped to the end of the table: no rows left
+    assert (o[3, :, 24:] == 0).all()              # 1000 + length clamped to 1024: 24 rows
+    for bi, piece in enumerate([(0, 200), None, (0, 200), (1000, 24)]):
+        if piece is None:
+            continue
+        a, ln = piece
+        o1, _ = pa.prefill_chunk_paged(pat, cnt, idx, q[bi:bi + 1, :, a:a + ln].contiguous().cuda(), kpg, vpg,
+                                       tg[bi:bi + 1].contiguous(), a)
+        torch.cuda.synchronize()
+        assert torch.equal(o[bi:bi + 1, :, :ln], o1), bi

@@ -14,6 +14,7 @@ from test_gpu_decode import run_decode
 from test_gpu_decode_paged import test_paged_matches_oracle_and_contiguous as check_paged
 from test_gpu_prefill_chunk import test_chunks_equal_whole_prefill as check_chunks
 from test_gpu_prefill_chunk_paged import test_paged_chunks_equal_whole_prefill as check_paged_chunks
+from test_gpu_prefill_chunk_paged import test_batch_of_pieces_equals_each_piece_alone as check_batch_of_pieces
 from test_gpu_prefill_varlen import test_padded_batch as check_padded_batch
 
 pytestmark = pytest.mark.gpu
@@ -157,3 +158,39 @@ UNALIGNED_CASES = draw_unaligned_chunk_cases(20250305, 16)
 def test_random_unaligned_chunks(kind, args):
     print(kind, args, flush=True)
     {"chunk": check_chunks, "chunk_paged": check_paged_chunks}[kind](*args)
+
+
+def draw_batch_cases(seed, count):
+    """Pieces of several sequences in one launch against a paged cache."""
+    rng = random.Random(seed)
+    cases = []
+    for c in range(count):
+        hkv = rng.choice([1, 2, 4])
+        hq = hkv * rng.choice([1, 2, 4, 7])
+        d = rng.choice([64, 128])
+        W = rng.choice([0, 1, 2, 4, 5])
+        S = rng.choice([0, 1, 2])
+        B = rng.choice([64, 64, 128, 192, 256])
+        flags = rng.choice([pa.POWER, pa.POWER, 0])
+        if not flags and W < 1:
+            W = 1
+        n = rng.randint(1, 2000)
+        batch = rng.randint(1, 4)
+        if hq * batch * n > 30000:
+            hq, hkv = 4, 2
+        pieces = []
+        for _ in range(batch):
+            a = rng.choice([0, rng.randint(0, n - 1)])
+            pieces.append((a, rng.choice([0, 1, n - a, rng.randint(0, n - a)])))
+        q_rows = max(1, max(ln for _, ln in pieces)) + rng.choice([0, 0, 5, 100])
+        cases.append((n, B, W, S, hq, hkv, d, pieces, min(q_rows, ((n + B - 1) // B) * B), flags))
+    return cases
+
+
+BATCH_CASES = draw_batch_cases(20250306, 12)
+
+
+@pytest.mark.parametrize("args", BATCH_CASES, ids=[str(i) for i in range(len(BATCH_CASES))])
+def test_random_batches_of_pieces(args):
+    print(args, flush=True)
+    check_batch_of_pieces(*args)
