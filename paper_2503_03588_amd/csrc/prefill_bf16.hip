@@ -80,6 +80,8 @@ struct bf16_params {
   int32_t tasks;     // G * B / 32
   int32_t chunks;    // workgroups per (batch, kv head, query block)
   int32_t per_xcd;   // work items per XCD partition
+  int32_t xcd_split; // sequences of different lengths, one or two KV heads: XCDs that share a KV head's items (else 0)
+  int64_t per_kvh;   // ... and the items of one KV head
   int32_t chain;     // items may be chained in persistent workgroups
   int64_t total_wg;
   int64_t N;         // keys in the context: query q_start + r attends keys <= q_start + r, all of them < N
@@ -177,7 +179,18 @@ void pa_prefill_bf16_kernel(bf16_params p) {
   // the workgroups of one XCD (one L2) work on neighbouring query blocks at any time ----
   const int xcd = pid & 7, cuslot = pid >> 3, nslots = (int)(gridDim.x >> 3);
   int n_raw = 0;                       // item numbers that fall to this workgroup
-  {
+  int64_t first_item = (int64_t)xcd * p.per_xcd + cuslot;
+  int item_step = nslots;
+  if (VARLEN && p.xcd_split > 1) {
+    // Sequences of different lengths and 1 or 2 KV heads: the XCDs that share a KV head take its item numbers
+    // in turn (number m goes to XCD m mod split of the head's group) instead of a contiguous part each, which would
+    // be some of the sequences and as much work as those happen to have.
+    const int sub = xcd % p.xcd_split;
+    const int64_t m0 = sub + (int64_t)p.xcd_split * cuslot;
+    item_step = p.xcd_split * nslots;
+    if (m0 < p.per_kvh) n_raw = (int)((p.per_kvh - m0 + item_step - 1) / item_step);
+    first_item = (int64_t)(xcd / p.xcd_split) * p.per_kvh + m0;
+  } else {
     int64_t lim = p.total_wg - (int64_t)xcd * p.per_xcd;
     if (lim > p.per_xcd) lim = p.per_xcd;
     if (lim > cuslot) n_raw = (int)((lim - cuslot + nslots - 1) / nslots);
@@ -229,7 +242,7 @@ void pa_prefill_bf16_kernel(bf16_params p) {
     it.i = 0; it.subs_diag = 0; it.n = 0; it.qs = 0;
     return it;
   };
-  const item_t stride = digits((uint32_t)nslots);
+  const item_t stride = digits((uint32_t)item_step);
   auto next_item = [&](const item_t& cur) -> item_t {
     item_t it = cur;
     it.chunk += stride.chunk; if (it.chunk >= p.chunks) { it.chunk -= p.chunks; ++it.r; }
@@ -505,7 +518,7 @@ void pa_prefill_bf16_kernel(bf16_params p) {
   };
 
   // ---- start of the stream: tables of the first two items, fills 0..NS-2, Q of the first item ----
-  it = digits((uint32_t)((int64_t)xcd * p.per_xcd + cuslot));
+  it = digits((uint32_t)first_item);
   finish_item(it);
   if (VARLEN) {
     // count this workgroup's existing items, then set out on the first three
@@ -986,7 +999,13 @@ int pa_launch_prefill_bf16(const pa_prefill_args& a) {
   // block positions instead of returning to the same few, whose rows exist for different shares of the batch.
   if (a.seq_len_dev && (p.nb & 1) == 0) ++p.nb;
   p.total_wg = (int64_t)a.batch * a.hkv * p.nb * p.chunks;
-  const int64_t per_xcd = (p.total_wg + 7) / 8;
+  int64_t per_xcd = (p.total_wg + 7) / 8;
+  p.xcd_split = 0; p.per_kvh = 0;
+  if (a.seq_len_dev && a.hkv <= 2) {   // (with four KV heads the contiguous halves measure the same or 1-2 % better)
+    p.xcd_split = 8 / a.hkv;
+    p.per_kvh = (int64_t)a.batch * p.nb * p.chunks;
+    per_xcd = (p.per_kvh + p.xcd_split - 1) / p.xcd_split;
+  }
   if (per_xcd * 8 > 0x7fffffffLL) return POWATTN_UNSUPPORTED;
   p.per_xcd = (int32_t)per_xcd;
   // chaining keeps the list row of the item after next in 63 lanes and two tile tables in LDS
