@@ -220,3 +220,53 @@ def test_batch_lengths_out_of_range_are_clamped():
                                        tg[bi:bi + 1].contiguous(), a)
         torch.cuda.synchronize()
         assert torch.equal(o[bi:bi + 1, :, :ln], o1), bi
+
+
+def test_batch_of_pieces_replayed_from_a_hip_graph_with_new_lengths():
+    # Starts and lengths are read by the kernel, so one captured launch serves successive serving steps: capture
+    # once, then replay with other (start, length) pairs written into the same device arrays, with eager calls in
+    # between, and compare every replay with the eager result of the same step.
+    pat = pa.Pattern(64, 4, 1)
+    n, hq, hkv, d, q_rows, batch = 2600, 8, 2, 128, 512, 3
+    q, k, v = synth.qkv(batch, hq, hkv, n, d, "bf16", seed=81)
+    kp, vp, table = pool_for(k, v, [n] * batch, 64, n_extra=2, seed=82)
+    kpg, vpg, tg, qg = kp.cuda(), vp.cuda(), table.cuda(), q.cuda()
+    cnt, idx, _ = pa.mask_build(pat, table.shape[1] * 64)
+    steps = [[(0, 512), (100, 300), (2000, 1)], [(512, 512), (400, 512), (2001, 1)], [(1024, 77), (912, 0), (2002, 511)]]
+    qb = torch.zeros((batch, hq, q_rows, d), dtype=torch.bfloat16, device="cuda")
+    starts = torch.zeros(batch, dtype=torch.int32, device="cuda")
+    lens = torch.zeros(batch, dtype=torch.int32, device="cuda")
+    o_g = torch.zeros_like(qb)
+    l_g = torch.zeros((batch, hq, q_rows), dtype=torch.float32, device="cuda")
+
+    def load(step):
+        qb.zero_()
+        for bi, (a, ln) in enumerate(step):
+            qb[bi, :, :ln] = qg[bi, :, a:a + ln]
+        starts.copy_(torch.tensor([a for a, _ in step], dtype=torch.int32))
+        lens.copy_(torch.tensor([ln for _, ln in step], dtype=torch.int32))
+
+    load(steps[0])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm up on the capture stream (one-time launch set-up)
+        pa.prefill_batch_paged(pat, cnt, idx, qb, kpg, vpg, tg, starts, lens, o=o_g, lse=l_g, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        pa.prefill_batch_paged(pat, cnt, idx, qb, kpg, vpg, tg, starts, lens, o=o_g, lse=l_g)
+    for rep in range(6):
+        step = steps[rep % 3]
+        load(step)
+        o_e = torch.full_like(qb, 7.0)
+        l_e = torch.full_like(l_g, 7.0)
+        pa.prefill_batch_paged(pat, cnt, idx, qb, kpg, vpg, tg, starts, lens, o=o_e, lse=l_e)   # eager, between replays
+        o_g.fill_(7.0); l_g.fill_(7.0)
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(o_g, o_e) and torch.equal(l_g, l_e), rep
+        for bi, (a, ln) in enumerate(step):
+            assert (o_g[bi, :, ln:] == 7.0).all(), (rep, bi)
+            if ln:
+                assert torch.isfinite(o_g[bi, :, :ln].float()).all() and (o_g[bi, :, :ln] != 7.0).any(), (rep, bi)
