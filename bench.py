@@ -249,6 +249,18 @@ def main():
     row = pa.row_host(pat_d, (Dc["len"] - 1) // Dc["B"])
     decode_bytes = len(row) * Dc["B"] * Dc["d"] * 2 * 2 * Dc["hkv"] * Dc["batch"]   # attended K and V tokens
     decode_gbs = decode_bytes / (decode_us * 1e-6) / 1e9
+    # The full-attention decode step on the same caches, for the ratio the paper reports for decoding (Section 4.3):
+    # the same kernel under a sliding window that spans the whole cache (all 1024 blocks of every sequence attended).
+    pat_dd = pa.Pattern(Dc["B"], Dc["len"] // Dc["B"] + 1, 0, 0)
+    ws_dd = pa.decode_workspace(pat_dd, Dc["batch"], Dc["hq"], Dc["hkv"], Dc["d"], Dc["cap"])
+    dd_us = time_batches(lambda s: pa.decode(pat_dd, qd, *caches[s % len(caches)], lens, o=od, lse=lsed, workspace=ws_dd),
+                         4, 5, warm=len(caches))
+    dd_bytes = Dc["len"] * Dc["d"] * 2 * 2 * Dc["hkv"] * Dc["batch"]
+    decode_dense = {"pattern": "sliding window over the whole cache (every key attended)", "us_per_step": stats(dd_us),
+                    "bytes_per_step": dd_bytes, "GB_per_s": round(dd_bytes / (statistics.fmean(dd_us) * 1e-6) / 1e9, 1),
+                    "frac_of_hbm_peak": round(dd_bytes / (statistics.fmean(dd_us) * 1e-6) / 1e9 / PEAK_HBM_GBS, 4),
+                    "dense_over_sparse": round(statistics.fmean(dd_us) / decode_us, 1), "bytes_ratio": round(dd_bytes / decode_bytes, 1)}
+    del ws_dd
 
     # The same step over a paged cache (powattn_decode_paged): the caches' memory read as a pool of pages of one
     # block each, every sequence's blocks on random pages of the whole pool (26 GB: cold), several tables in
@@ -711,6 +723,7 @@ def main():
                                 "frac_in_step": round(decode_bytes / (decode_in_step_us * 1e-6) / 1e9 / PEAK_HBM_GBS, 4),
                                 "bytes_per_step": decode_bytes,
                                 "traffic": (traffic("decode") or {}).get("bytes"), "traffic_measured_on": traffic("decode")},
+                   "full_attention_same_caches": decode_dense,
                    "context_131072": decode_128k,
                    "paged_cache_by_batch": paged},
         "measured_peaks": measured_peaks,

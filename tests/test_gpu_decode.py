@@ -54,6 +54,16 @@ def test_sliding_window_flag_and_scale():
     run_decode(pa.Pattern(64, 5, 1, flags=0), 2, 4, 2, 2048, 128, [2048, 900], seed=32, scale=0.11)
 
 
+@pytest.mark.parametrize("B,hq,hkv,d,cap,kv_len", [
+    (64, 8, 2, 128, 8192, [8192, 8191, 4097, 65, 1]),      # up to 128 chunks per (sequence, KV head)
+    (128, 4, 1, 64, 16384, [16384, 9000]),                   # up to 256 chunks
+])
+def test_window_over_the_whole_cache_is_full_attention(B, hq, hkv, d, cap, kv_len):
+    # a sliding window of as many blocks as the cache has attends every key: the dense decode step that bench.py
+    # times beside the sparse one
+    run_decode(pa.Pattern(B, cap // B + 1, 0, flags=0), len(kv_len), hq, hkv, cap, d, kv_len, seed=34, calls=2)
+
+
 def test_peaked_scores():
     # softmax scale 1 on N(0,1) inputs: logits with a standard deviation of ~11, nearly one-hot rows; 25 chunks per
     # row, so a wavefront meets larger and larger maxima over its passes and the workgroups' partials differ widely
