@@ -241,8 +241,11 @@ int powattn_prefill_batch_paged(const powattn_pattern* pattern,
  *   d_kv_cnt, d_kv_idx, max_k   lists covering ceil(padded_len / block) rows
  *   dtype          POWATTN_BF16 only; head_dim 64 or 128; block a multiple of 64, at most 1024
  * Work is dealt to the compute units by position in the padded batch, not by
- * length: a batch whose long sequences sit next to one another is balanced less
- * well than a shuffled one.
+ * length, in an order that keeps them level for any mix of lengths when there
+ * are 1, 2 or a multiple of 8 KV heads (every part of the chip then sees every
+ * sequence); with other head counts a part sees some of the sequences, and a
+ * batch whose long sequences sit next to one another is balanced less well
+ * than a shuffled one.
  * Errors: INVALID_ARG, UNSUPPORTED, HIP_ERROR.
  */
 int powattn_prefill_varlen(const powattn_pattern* pattern,
