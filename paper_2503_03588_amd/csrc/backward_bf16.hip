@@ -4,11 +4,12 @@
 // With P the softmax (recomputed from the saved log-sum-exp), dP = dO V^T, Delta_i = sum_d dO_id O_id and
 // dS = P * (dP - Delta):   dQ = scale dS K,   dK = scale dS^T Q,   dV = P^T dO.
 //
-// Three kernels:
-//   delta : Delta = rowsum(dO * O), one fp32 per (batch, query head, token), and the log-sum-exp in base 2
+// Two kernels:
 //   dq    : a workgroup per (batch, KV head, query block, group of query-head slices) walks the row's key blocks
 //           (the lists powattn_mask_build writes), as the forward pass does; wavefront = 32 queries of one head,
 //           lane = one query.  S^T = K Q^T and dP^T = V dO^T share the K/V tiles in LDS; dQ^T += K^T dS^T.
+//           It also forms Delta = rowsum(dO * O) of its rows (dO is in its registers anyway) and leaves it, with
+//           the log-sum-exp in base-2 units, in the workspace for the kernel below.
 //   dkv   : a workgroup per (batch, KV head, key block) walks the COLUMN of the block mask: the query blocks
 //           j .. j+W-1 and j + 2^k (closed form), all of them for a sink block; wavefront = 32 keys, lane = one key.
 //           Q and dO tiles of 64 queries go through LDS; dV^T += dO^T P, dK^T += Q^T dS.  A sink block's column is
@@ -196,30 +197,6 @@ __device__ __forceinline__ void pipelined_mfma(LoadF load, MmaF mma) {
 // Element rg (0..15) of a 32x32 accumulator is row 8(rg/4) + 4(lane/32) + rg%4, column lane%32.
 __device__ __forceinline__ int acc_row(int rg, int hh) { return 8 * (rg >> 2) + 4 * hh + (rg & 3); }
 
-// ---------------------------------------------------------------------------------------------------------------
-// Delta = rowsum(dO * O)
-// ---------------------------------------------------------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(256) void pa_bwd_delta_kernel(const __bf16* o, const __bf16* dout, const float* lse, float* delta,
-                                                           float* lse2, int64_t rows) {
-  constexpr int LPR = D / 8;                 // lanes per row
-  const int64_t row = ((int64_t)blockIdx.x * 256 + threadIdx.x) / LPR;
-  const int sub = threadIdx.x % LPR;
-  float s = 0.f;
-  if (row < rows) {
-    const bf16x8 a = *reinterpret_cast<const bf16x8*>(o + row * D + 8 * sub);
-    const bf16x8 b = *reinterpret_cast<const bf16x8*>(dout + row * D + 8 * sub);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) s = fmaf((float)a[e], (float)b[e], s);
-  }
-#pragma unroll
-  for (int m = LPR / 2; m >= 1; m >>= 1) s += __shfl_xor(s, m);
-  if (row < rows && sub == 0) {
-    delta[row] = s;
-    lse2[row] = lse[row] * LOG2E;
-  }
-}
-
 __global__ __launch_bounds__(256) void pa_bwd_zero_kernel(float* p, int64_t n) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i < n) p[i] = 0.f;
@@ -304,8 +281,25 @@ void pa_bwd_dq_kernel(bwd_params p) {
   bf16x8 qf[NC], dof[NC];
   reg_rows<D>(p.q + qrow * D, ok, lane, qf);
   reg_rows<D>(p.dout + qrow * D, ok, lane, dof);
-  const float lse2 = ok ? p.lse2[qrow] : INFINITY;               // exp2(s - inf) = 0: idle lanes contribute nothing
-  const float dl = ok ? p.delta[qrow] : 0.f;
+  // Delta = rowsum(dO * O) of this lane's row and its log-sum-exp in base-2 units: formed here, where the row of dO
+  // is in registers anyway (the two halves of the wavefront hold the two halves of the row), and left in the
+  // workspace for the dK/dV kernel, which follows on the stream.  Every row belongs to exactly one task.
+  float lse2 = INFINITY, dl = 0.f;                               // exp2(s - inf) = 0: idle lanes contribute nothing
+  {
+    bf16x8 of[NC];
+    reg_rows<D>(p.o + qrow * D, ok, lane, of);
+    float part = 0.f;
+#pragma unroll
+    for (int c = 0; c < NC; ++c)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) part = fmaf((float)of[c][e], (float)dof[c][e], part);
+    part += __shfl_xor(part, 32);
+    if (ok) {
+      dl = part;
+      lse2 = p.lse[qrow] * LOG2E;
+      if (hh == 0) { p.delta[qrow] = dl; p.lse2[qrow] = lse2; }
+    }
+  }
   const int tok32 = (int)tok, n32 = (int)p.N;                    // positions fit 32 bits (checked by the host)
 
   f32x16 acc[ND];
@@ -874,16 +868,7 @@ int pa_launch_backward_bf16(const pa_backward_args& a) {
   ws += align256((size_t)sink_elems * sizeof(float));
   p.dv_sink = (float*)ws;
 
-  const int64_t rows = (int64_t)a.batch * a.hq * a.seq_len;
-  const int lpr = a.head_dim / 8;
-  const int64_t dblocks = (rows * lpr + 255) / 256;
-  if (dblocks > 0x7fffffffLL) return POWATTN_UNSUPPORTED;
-  if (a.head_dim == 128)
-    hipLaunchKernelGGL((pa_bwd_delta_kernel<128>), dim3((uint32_t)dblocks), dim3(256), 0, a.stream, p.o, p.dout, p.lse, p.delta, p.lse2, rows);
-  else
-    hipLaunchKernelGGL((pa_bwd_delta_kernel<64>), dim3((uint32_t)dblocks), dim3(256), 0, a.stream, p.o, p.dout, p.lse, p.delta, p.lse2, rows);
-  int st = pa_note_hip(hipGetLastError());
-  if (st != POWATTN_OK) return st;
+  int st = POWATTN_OK;
   if (sink_elems > 0) {
     const int64_t zb = (2 * (int64_t)(align256((size_t)sink_elems * sizeof(float)) / sizeof(float)) + 255) / 256;
     hipLaunchKernelGGL(pa_bwd_zero_kernel, dim3((uint32_t)zb), dim3(256), 0, a.stream, p.dk_sink,
