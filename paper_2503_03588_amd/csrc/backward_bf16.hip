@@ -397,9 +397,12 @@ __global__ __launch_bounds__(64 * NW) void pa_bwd_dkv_kernel(bwd_params p) {
 
   // ---- which key block, which part of its column ----
   int j, part;
-  if ((int)blockIdx.x < p.nb) { j = blockIdx.x; part = 0; }
+  // the parts of the sink blocks' columns come first in the launch: they are the longest workgroups (PART query
+  // blocks each against a dozen for an ordinary column), and the last ones to start should be the shortest
+  const int n_extra = p.sink_blocks * (p.max_parts - 1);
+  if ((int)blockIdx.x >= n_extra) { j = (int)blockIdx.x - n_extra; part = 0; }
   else {
-    const int e = (int)blockIdx.x - p.nb;
+    const int e = (int)blockIdx.x;
     j = e / (p.max_parts - 1);
     part = 1 + e % (p.max_parts - 1);
   }
@@ -603,9 +606,12 @@ void pa_bwd_dkv_split_kernel(bwd_params p) {
   const bool krole = wave >= NSL;                // false: S, P, dV^T; true: dP, dS, dK^T
 
   int j, part;
-  if ((int)blockIdx.x < p.nb) { j = blockIdx.x; part = 0; }
+  // the parts of the sink blocks' columns come first in the launch: they are the longest workgroups (PART query
+  // blocks each against a dozen for an ordinary column), and the last ones to start should be the shortest
+  const int n_extra = p.sink_blocks * (p.max_parts - 1);
+  if ((int)blockIdx.x >= n_extra) { j = (int)blockIdx.x - n_extra; part = 0; }
   else {
-    const int e = (int)blockIdx.x - p.nb;
+    const int e = (int)blockIdx.x;
     j = e / (p.max_parts - 1);
     part = 1 + e % (p.max_parts - 1);
   }
