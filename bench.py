@@ -36,9 +36,9 @@ PEAK_HBM_GBS = 8000.0            # MI355X HBM3E peak
 # the kernel and the grid it was taken on (profiles/*.md hold the runs); it is reported only while the library
 # that is loaded still has that version (the version number moves with every change to a kernel), else null.
 TRAFFIC = {
-    "prefill": {"bytes": 5.42e9, "library_version": 107, "kernel": "pa_prefill_bf16_kernel<128,8,4,false,true,false,false>",
+    "prefill": {"bytes": 5.42e9, "library_version": 108, "kernel": "pa_prefill_bf16_kernel<128,8,4,false,true,false,false>",
                 "grid": 256, "source": "profiles/prefill_bf16_128k_pmc.md"},
-    "decode": {"bytes": 57.6e6, "library_version": 107, "kernel": "pa_decode_kernel<128>", "grid": [2, 8, 16],
+    "decode": {"bytes": 57.6e6, "library_version": 108, "kernel": "pa_decode_kernel<128>", "grid": [2, 8, 16],
                "source": "profiles/decode_b16_64k_pmc.md"},
 }
 

@@ -5,7 +5,7 @@
 #include "../../include/powattn.h"
 #include "pattern.h"
 
-#define POWATTN_VERSION_NUMBER 107  // 0.1.7; moves with every change to a kernel (bench.py ties its profiled traffic figures to it)
+#define POWATTN_VERSION_NUMBER 108  // 0.1.8; moves with every change to a kernel (bench.py ties its profiled traffic figures to it)
 
 // Records a HIP error for powattn_strerror and maps it to a status.
 int pa_note_hip(hipError_t e);
