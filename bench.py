@@ -515,11 +515,19 @@ def main():
         csum_b = np.concatenate([[0], np.cumsum(c_b.cpu().numpy().astype(np.int64))])
         pairs_b = int(sum(csum_b[(int(a) + int(n) - 1) // Bp["B"] + 1] - csum_b[int(a) // Bp["B"]] for a, n in zip(st_np, ln_np)))
         f_b = flops_block(Bp["B"], Bp["d"], Bp["hq"], 1, pairs_b)
+        # two of the sequences once more, each alone through powattn_prefill_chunk_paged: must agree bit for bit
+        same_b = True
+        for bi in (0, int(np.argmax(st_np.astype(np.int64) + ln_np))):
+            a_, n_ = int(st_np[bi]), int(ln_np[bi])
+            o_1, _ = pa.prefill_chunk_paged(pat_b, c_b, i_b, q_b[bi:bi + 1, :, :n_].contiguous(), kp_b, vp_b,
+                                            tab_b[bi:bi + 1].contiguous(), a_, want_lse=False)
+            same_b = same_b and bool(torch.equal(o_1, o_b[bi:bi + 1, :, :n_]))
         batch_paged = {"workload": "32 sequences, contexts so far 0..63K tokens (seeded uniform, any offset), pieces of 256..2048 new "
                                    "rows padded to 2048, 32q/8kv heads, D=128, block 64, W=4, S=1, bf16; K/V in a shuffled pool of "
                                    "%d pages; one launch, starts and lengths read on the device" % n_pages_b,
                        "new_tokens": int(ln_np.sum()), "attended_block_pairs_whole_blocks": pairs_b, "kernel_ms": ms_b,
-                       "tflops": round(f_b / (ms_b["mean"] * 1e-3) / 1e12, 1)}
+                       "tflops": round(f_b / (ms_b["mean"] * 1e-3) / 1e12, 1),
+                       "two_sequences_bit_identical_to_single_calls": same_b}
         del kp_b, vp_b, q_b, o_b
 
     # ---------------- a serving batch of prompts of different lengths in one launch (powattn_prefill_varlen,
